@@ -1,0 +1,160 @@
+/*
+ * vattn.h - C ABI of the MI355X (gfx950) contiguous-KV attention library.
+ *
+ * The library implements the hot path that the vAttention paper (arXiv 2405.04437) speeds up:
+ * every request's K and V cache is ONE virtually contiguous tensor; physical memory is mapped under
+ * it on demand with the HIP virtual-memory calls, and the attention kernels read K/V with plain
+ * pointer arithmetic - there is no block table inside any kernel.
+ *
+ * Conventions
+ *  - All functions are extern "C", take plain pointers and sizes, and return int: >= 0 on success,
+ *    -1 on failure (as the paper's step() does).  vattn_last_error() returns a thread-local,
+ *    NUL-terminated description of the most recent failure on the calling thread.
+ *  - "host" / "device" in a parameter comment says where the pointer must point.
+ *  - Index arrays (reqids, cu_q, kv_lens, seq_lens) are HOST pointers; the library validates them
+ *    and uploads what the kernels need.  They may be reused as soon as the call returns.
+ *  - Q, O, new K/V rows and the decode workspace are DEVICE pointers owned by the caller.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels are enqueued,
+ *    never synchronised: results are ready when the stream reaches them.
+ *  - The library owns all virtual reservations and physical handles from vattn_init() until
+ *    vattn_destroy().
+ *  - A context is not thread-safe: calls on one context must be serialised by the caller.
+ *
+ * Notation follows the paper's Table 2: N layers, H KV heads, D head dimension, P bytes per
+ * element, B maximum batch size, L maximum context length; Hq query heads (Table 5).
+ */
+#ifndef VATTN_H
+#define VATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vattn_ctx vattn_ctx; /* opaque */
+
+/* Policy for what free_reqid does with a request's pages (Sec. 5.3.4 "may unmap the physical
+ * pages of a completed request or defer them", Sec. 6.1.2 deferred reclamation). */
+#define VATTN_POLICY_SYNC_UNMAP 0u /* free_reqid unmaps everything at once                      */
+#define VATTN_POLICY_DEFERRED 1u   /* pages stay mapped; alloc_reqid prefers the best-backed id;
+                                      step() reclaims from inactive ids only when the pool is short */
+
+/* Arguments of init() in Table 4: N, B, L, H, D, P, page-group size (plus what a C library needs). */
+typedef struct {
+    int32_t num_layers;        /* N                                                               */
+    int32_t max_batch;         /* B: reqIds are 0 .. B-1                                          */
+    int64_t max_ctx;           /* L: tokens per request the reservation must hold                 */
+    int32_t num_q_heads;       /* Hq, a multiple of H                                             */
+    int32_t num_kv_heads;      /* H                                                               */
+    int32_t head_dim;          /* D: 64 or 128                                                    */
+    int32_t elem_bytes;        /* P: 2 (bf16)                                                     */
+    int64_t page_group_bytes;  /* 0 = 2 MiB; otherwise a multiple of the granularity reported by
+                                  hipMemGetAllocationGranularity                                  */
+    int64_t phys_budget_bytes; /* size of the physical page-group pool created at init, summed
+                                  over all 2N buffers; rounded down to whole page-groups          */
+    int32_t device;            /* HIP device ordinal                                              */
+    uint32_t flags;            /* VATTN_POLICY_*                                                  */
+} vattn_config;
+
+/* ---- memory management: Table 4 and Algorithm 1 of the paper -------------------------------- */
+
+/* init (Table 4; Sec. 5.3.1): reserves 2N virtual buffers of B*S bytes each, S = L*H*D*P rounded
+ * up to the page-group size (Sec. 5.1.3), and creates the physical page-group pool WITHOUT mapping
+ * any of it.  *out receives the context.  Fails if the device lacks virtual-memory support, the
+ * configuration is invalid, or the pool cannot be created. */
+int vattn_init(const vattn_config* cfg /*host*/, vattn_ctx** out /*host*/);
+
+/* Unmaps and releases everything, frees the reservations and the context.  The caller must have
+ * synchronised all streams that still use the KV buffers. */
+int vattn_destroy(vattn_ctx* ctx);
+
+/* alloc_reqid (Table 4): marks an unused reqId active and returns it, or -1 if all B are in use.
+ * SYNC_UNMAP: the lowest unused id.  DEFERRED: the unused id with the most page-groups still
+ * mapped (Sec. 6.1.2), ties to the lowest id. */
+int vattn_alloc_reqid(vattn_ctx* ctx);
+
+/* free_reqid (Table 4; Sec. 5.3.4): marks reqId inactive.  SYNC_UNMAP: also unmaps all its
+ * page-groups in all 2N buffers and returns them to the pool - the caller must make sure no
+ * enqueued kernel still reads them.  DEFERRED: leaves them mapped.  -1 if reqid is out of range or
+ * not active. */
+int vattn_free_reqid(vattn_ctx* ctx, int reqid);
+
+/* step (Table 4; Sec. 5.3.3): seq_lens[count], count == B, holds the context length of every
+ * reqId (0 for inactive ids).  On return 0, every active request has at least
+ * ceil(len*H*D*P / page_group_bytes) page-groups mapped, contiguously from its base, in each of the
+ * 2N buffers.  All-or-nothing: if the pool (plus, under DEFERRED, pages held by inactive ids)
+ * cannot cover the demand, or an argument is invalid (wrong count, len > L, non-zero length for an
+ * inactive id), it returns -1 and changes nothing.  Lengths that shrink never unmap. */
+int vattn_step(vattn_ctx* ctx, const int64_t* seq_lens /*host*/, int count);
+
+/* Request-level indexing (Sec. 5.2.3): device address of reqId's sub-tensor in layer `layer`,
+ * which = 0 for K, 1 for V: buffer base + reqId*S.  Layout inside: [L, H, D], token-major.
+ * NULL on an invalid argument.  Only the first mapped_page_groups*page_group_bytes bytes may be
+ * touched. */
+void* vattn_kv_ptr(vattn_ctx* ctx, int layer, int which, int reqid);
+
+/* Introspection for tests: active flag, page-groups mapped per sub-tensor (identical in all 2N
+ * buffers) and the byte offset reqId*S of the sub-tensor inside each buffer. */
+int vattn_query(vattn_ctx* ctx, int reqid, int* active, int64_t* mapped_page_groups, int64_t* va_offset);
+
+/* Page-group size in bytes, S, pool size and free pool count (both in page-groups). */
+int vattn_stats(vattn_ctx* ctx, int64_t* page_group_bytes, int64_t* S_bytes, int64_t* pool_total,
+                int64_t* pool_free);
+
+/* Cumulative number of (buffer, page-group) map and unmap operations, and the wall time in
+ * microseconds the library spent inside hipMemMap+hipMemSetAccess and hipMemUnmap. */
+int vattn_counters(vattn_ctx* ctx, int64_t* map_calls, int64_t* unmap_calls, double* map_us, double* unmap_us);
+
+/* ---- the attention path (Eq. 2 of the paper, evaluated per request) -------------------------- */
+
+/* KV append ("a single tensor copy", Sec. 7.1): copies the new rows k_new/v_new [sum q_len, H, D]
+ * (device, bf16) of n requests to token positions kv_len_before[r] .. kv_len_before[r]+q_len-1 of
+ * each request's K and V sub-tensor in `layer`.  cu_q[n+1] are prefix sums of q_len.  The target
+ * range must already be mapped by step(). */
+int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new /*device*/,
+                    const void* v_new /*device*/, const int32_t* reqids /*host*/,
+                    const int32_t* cu_q /*host*/, const int64_t* kv_len_before /*host*/, int n);
+
+/* Causal prefill attention.  q, o: [sum q_len, Hq, D] bf16 (device), packed over the n requests in
+ * order; kv_lens[r] is the context length AFTER the q_len newest tokens were appended, so query
+ * row i of request r attends to keys 0 .. kv_lens[r]-q_len+i (a chunk appended to an existing
+ * context sees all of it).  Query head h reads KV head h/(Hq/H).  scores are multiplied by `scale`
+ * (Eq. 2 divides by "scale"; pass 1/sqrt(D)).  reqids[r] selects the KV sub-tensor of batch slot r
+ * (the batch-index indirection of Sec. 5.3.4).  fp32 accumulation, bf16 output. */
+int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q /*device*/,
+                       void* o /*device*/, const int32_t* reqids /*host*/, const int32_t* cu_q /*host*/,
+                       const int64_t* kv_lens /*host*/, int n, float scale);
+
+/* Bytes of device workspace vattn_attn_decode needs for these context lengths (split-K partial
+ * results).  -1 on an invalid argument. */
+int64_t vattn_decode_workspace_bytes(vattn_ctx* ctx, const int64_t* kv_lens /*host*/, int n);
+
+/* Decode attention, one query token per request: q, o [n, Hq, D] bf16 (device).  Runs a split-K
+ * kernel over fixed-size token chunks of every request's context followed by a reduce kernel that
+ * merges the chunk partials (running maximum and sum) and writes bf16.  workspace: device memory
+ * of at least vattn_decode_workspace_bytes(), 256-byte aligned, private to this call until the
+ * stream has passed it. */
+int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q /*device*/,
+                      void* o /*device*/, const int32_t* reqids /*host*/, const int64_t* kv_lens /*host*/,
+                      int n, float scale, void* workspace /*device*/, size_t workspace_bytes);
+
+/* ---- measurement helpers --------------------------------------------------------------------- */
+
+/* When enabled, every launch of the split-K decode kernel and of the prefill kernel is bracketed
+ * by HIP events on the launch stream; vattn_kernel_time() then synchronises those events and
+ * returns the accumulated kernel time in milliseconds and the number of launches since the last
+ * call, per kernel (which: 0 = decode split-K, 1 = prefill, 2 = decode reduce), and resets them. */
+int vattn_set_timing(vattn_ctx* ctx, int enabled);
+int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* launches);
+
+/* Tuning knob: tokens per split-K chunk (multiple of 32; 0 = choose from the batch). */
+int vattn_set_decode_chunk(vattn_ctx* ctx, int tokens);
+
+const char* vattn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VATTN_H */

@@ -1,0 +1,186 @@
+"""Thin ctypes binding of libvattn.so: argument marshalling only.
+
+Every step of the path (memory mapping, KV append, prefill and decode attention) runs inside the
+library; nothing here computes.  The function names match the C ABI declared in include/vattn.h.
+If the shared library has not been built the import fails loudly - there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvattn.so")
+
+POLICY_SYNC_UNMAP = 0
+POLICY_DEFERRED = 1
+
+
+class VattnError(RuntimeError):
+    pass
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [("num_layers", ctypes.c_int32), ("max_batch", ctypes.c_int32), ("max_ctx", ctypes.c_int64),
+                ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("elem_bytes", ctypes.c_int32), ("page_group_bytes", ctypes.c_int64),
+                ("phys_budget_bytes", ctypes.c_int64), ("device", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2405_04437_amd.build` "
+                          "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32p, i64p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    lib.vattn_last_error.restype = ctypes.c_char_p
+    lib.vattn_init.argtypes = [ctypes.POINTER(_Config), ctypes.POINTER(vp)]
+    lib.vattn_destroy.argtypes = [vp]
+    lib.vattn_alloc_reqid.argtypes = [vp]
+    lib.vattn_free_reqid.argtypes = [vp, ctypes.c_int]
+    lib.vattn_step.argtypes = [vp, i64p, ctypes.c_int]
+    lib.vattn_kv_ptr.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    lib.vattn_kv_ptr.restype = vp
+    lib.vattn_query.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_int), i64p, i64p]
+    lib.vattn_stats.argtypes = [vp, i64p, i64p, i64p, i64p]
+    lib.vattn_counters.argtypes = [vp, i64p, i64p, dp, dp]
+    lib.vattn_append_kv.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32p, i32p, i64p, ctypes.c_int]
+    lib.vattn_attn_prefill.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32p, i32p, i64p, ctypes.c_int, ctypes.c_float]
+    lib.vattn_decode_workspace_bytes.argtypes = [vp, i64p, ctypes.c_int]
+    lib.vattn_decode_workspace_bytes.restype = ctypes.c_int64
+    lib.vattn_attn_decode.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32p, i64p, ctypes.c_int, ctypes.c_float, vp,
+                                      ctypes.c_size_t]
+    lib.vattn_set_timing.argtypes = [vp, ctypes.c_int]
+    lib.vattn_kernel_time.argtypes = [vp, ctypes.c_int, dp, i64p]
+    lib.vattn_set_decode_chunk.argtypes = [vp, ctypes.c_int]
+    for name in ("vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_query",
+                 "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill", "vattn_attn_decode",
+                 "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk"):
+        getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+lib = _load()
+
+EXPORTED = ["vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_kv_ptr",
+            "vattn_query", "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill",
+            "vattn_decode_workspace_bytes", "vattn_attn_decode", "vattn_set_timing", "vattn_kernel_time",
+            "vattn_set_decode_chunk", "vattn_last_error"]
+
+
+def last_error() -> str:
+    return (lib.vattn_last_error() or b"").decode()
+
+
+def _i32(a: Sequence[int]):
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _i64(a: Sequence[int]):
+    arr = np.ascontiguousarray(a, dtype=np.int64)
+    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+
+
+def _ptr(x) -> int:
+    """Device address of a torch tensor, or an int passed through."""
+    return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
+
+
+class Vattn:
+    """One library context; method names mirror the C entry points without the prefix."""
+
+    def __init__(self, num_layers: int, max_batch: int, max_ctx: int, num_q_heads: int, num_kv_heads: int,
+                 head_dim: int, phys_budget_bytes: int, page_group_bytes: int = 0, elem_bytes: int = 2,
+                 device: int = 0, policy: int = POLICY_SYNC_UNMAP) -> None:
+        cfg = _Config(num_layers, max_batch, max_ctx, num_q_heads, num_kv_heads, head_dim, elem_bytes,
+                      page_group_bytes, phys_budget_bytes, device, policy)
+        h = ctypes.c_void_p()
+        if lib.vattn_init(ctypes.byref(cfg), ctypes.byref(h)) != 0:
+            raise VattnError("vattn_init: " + last_error())
+        self._h = h
+        self.max_batch = max_batch
+        self.num_q_heads, self.num_kv_heads, self.head_dim = num_q_heads, num_kv_heads, head_dim
+
+    def destroy(self) -> None:
+        if self._h:
+            lib.vattn_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # ---- Table 4 of the paper --------------------------------------------------------------
+    def alloc_reqid(self) -> int:
+        return lib.vattn_alloc_reqid(self._h)
+
+    def free_reqid(self, reqid: int) -> int:
+        return lib.vattn_free_reqid(self._h, reqid)
+
+    def step(self, seq_lens: Sequence[int]) -> int:
+        arr, p = _i64(seq_lens)
+        return lib.vattn_step(self._h, p, len(arr))
+
+    # ---- introspection ---------------------------------------------------------------------
+    def kv_ptr(self, layer: int, which: int, reqid: int) -> int:
+        return lib.vattn_kv_ptr(self._h, layer, which, reqid) or 0
+
+    def query(self, reqid: int) -> Tuple[int, int, int]:
+        a, m, o = ctypes.c_int(), ctypes.c_int64(), ctypes.c_int64()
+        if lib.vattn_query(self._h, reqid, ctypes.byref(a), ctypes.byref(m), ctypes.byref(o)) != 0:
+            raise VattnError(last_error())
+        return a.value, m.value, o.value
+
+    def stats(self) -> Tuple[int, int, int, int]:
+        v = [ctypes.c_int64() for _ in range(4)]
+        lib.vattn_stats(self._h, *[ctypes.byref(x) for x in v])
+        return tuple(x.value for x in v)
+
+    def counters(self) -> Tuple[int, int, float, float]:
+        a, b, c, d = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_double(), ctypes.c_double()
+        lib.vattn_counters(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d))
+        return a.value, b.value, c.value, d.value
+
+    # ---- attention path --------------------------------------------------------------------
+    def append_kv(self, layer: int, stream: int, k_new, v_new, reqids, cu_q, kv_len_before) -> int:
+        r, rp = _i32(reqids)
+        c, cp = _i32(cu_q)
+        b, bp = _i64(kv_len_before)
+        return lib.vattn_append_kv(self._h, layer, stream, _ptr(k_new), _ptr(v_new), rp, cp, bp, len(r))
+
+    def attn_prefill(self, layer: int, stream: int, q, o, reqids, cu_q, kv_lens, scale: float) -> int:
+        r, rp = _i32(reqids)
+        c, cp = _i32(cu_q)
+        k, kp = _i64(kv_lens)
+        return lib.vattn_attn_prefill(self._h, layer, stream, _ptr(q), _ptr(o), rp, cp, kp, len(r), scale)
+
+    def decode_workspace_bytes(self, kv_lens) -> int:
+        k, kp = _i64(kv_lens)
+        return lib.vattn_decode_workspace_bytes(self._h, kp, len(k))
+
+    def attn_decode(self, layer: int, stream: int, q, o, reqids, kv_lens, scale: float, workspace,
+                    workspace_bytes: int) -> int:
+        r, rp = _i32(reqids)
+        k, kp = _i64(kv_lens)
+        return lib.vattn_attn_decode(self._h, layer, stream, _ptr(q), _ptr(o), rp, kp, len(r), scale,
+                                     _ptr(workspace), workspace_bytes)
+
+    # ---- measurement -----------------------------------------------------------------------
+    def set_timing(self, enabled: bool) -> int:
+        return lib.vattn_set_timing(self._h, 1 if enabled else 0)
+
+    def kernel_time(self, which: int) -> Tuple[float, int]:
+        t, n = ctypes.c_double(), ctypes.c_int64()
+        if lib.vattn_kernel_time(self._h, which, ctypes.byref(t), ctypes.byref(n)) != 0:
+            raise VattnError(last_error())
+        return t.value, n.value
+
+    def set_decode_chunk(self, tokens: int) -> int:
+        return lib.vattn_set_decode_chunk(self._h, tokens)

@@ -1,0 +1,290 @@
+// C ABI of libvattn: argument checking, index marshalling and kernel launches.  All arithmetic of the
+// attention path runs in the HIP kernels; this file only validates, packs index arrays into a pinned
+// staging slot, uploads them on the caller's stream and launches.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "vattn_internal.h"
+
+namespace vattn { const std::string& last_error_string(); }
+using namespace vattn;
+
+namespace {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool check_ctx_layer(vattn_ctx* ctx, int layer, const char* fn) {
+    if (!ctx) { set_error(std::string(fn) + ": null context"); return false; }
+    if (layer < 0 || layer >= ctx->cfg.num_layers) { set_error(std::string(fn) + ": layer out of range"); return false; }
+    return true;
+}
+
+// A request may be attended to / appended to only if it is active and its context is fully backed.
+bool check_request(vattn_ctx* ctx, int reqid, int64_t kv_len, const char* fn) {
+    if (!ctx->mem.valid_reqid(reqid) || !ctx->mem.is_active(reqid)) {
+        set_error(std::string(fn) + ": reqId " + std::to_string(reqid) + " out of range or not active");
+        return false;
+    }
+    if (kv_len < 0 || kv_len > ctx->cfg.max_ctx || kv_len * ctx->mem.T() > ctx->mem.mapped(reqid) * ctx->mem.G()) {
+        set_error(std::string(fn) + ": context length " + std::to_string(kv_len) + " of reqId " + std::to_string(reqid) +
+                  " exceeds what step() has mapped");
+        return false;
+    }
+    return true;
+}
+
+int choose_chunk(const vattn_ctx* ctx, const int64_t* kv_lens, int n) {
+    if (ctx->decode_chunk > 0) return ctx->decode_chunk;
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) total += kv_lens[i];
+    // Aim for a few thousand chunk workgroups so that all 256 CUs hold several; never below 64 tokens.
+    int chunk = 512;
+    while (chunk > 64 && total / chunk < 2048) chunk >>= 1;
+    return chunk;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* vattn_last_error(void) { return last_error_string().c_str(); }
+
+int vattn_init(const vattn_config* cfg, vattn_ctx** out) {
+    if (!cfg || !out) { set_error("init: null argument"); return -1; }
+    vattn_ctx* ctx = new (std::nothrow) vattn_ctx();
+    if (!ctx) { set_error("init: out of host memory"); return -1; }
+    ctx->cfg = *cfg;
+    if (!ctx->mem.init(*cfg)) { delete ctx; return -1; }
+    *out = ctx;
+    return 0;
+}
+
+int vattn_destroy(vattn_ctx* ctx) {
+    if (!ctx) return 0;
+    for (auto& t : ctx->timers) t.destroy();
+    delete ctx;
+    return 0;
+}
+
+int vattn_alloc_reqid(vattn_ctx* ctx) { return ctx ? ctx->mem.alloc_reqid() : (set_error("alloc_reqid: null context"), -1); }
+int vattn_free_reqid(vattn_ctx* ctx, int reqid) { return ctx ? ctx->mem.free_reqid(reqid) : (set_error("free_reqid: null context"), -1); }
+int vattn_step(vattn_ctx* ctx, const int64_t* seq_lens, int count) { return ctx ? ctx->mem.step(seq_lens, count) : (set_error("step: null context"), -1); }
+
+void* vattn_kv_ptr(vattn_ctx* ctx, int layer, int which, int reqid) {
+    if (!check_ctx_layer(ctx, layer, "kv_ptr")) return nullptr;
+    if ((which != 0 && which != 1) || !ctx->mem.valid_reqid(reqid)) { set_error("kv_ptr: invalid argument"); return nullptr; }
+    return ctx->mem.sub_tensor(layer, which, reqid);
+}
+
+int vattn_query(vattn_ctx* ctx, int reqid, int* active, int64_t* mapped, int64_t* va_offset) {
+    if (!ctx || !ctx->mem.valid_reqid(reqid)) { set_error("query: invalid argument"); return -1; }
+    if (active) *active = ctx->mem.is_active(reqid) ? 1 : 0;
+    if (mapped) *mapped = ctx->mem.mapped(reqid);
+    if (va_offset) *va_offset = static_cast<int64_t>(reqid) * ctx->mem.S();
+    return 0;
+}
+
+int vattn_stats(vattn_ctx* ctx, int64_t* page_group_bytes, int64_t* S_bytes, int64_t* pool_total, int64_t* pool_free) {
+    if (!ctx) { set_error("stats: null context"); return -1; }
+    if (page_group_bytes) *page_group_bytes = ctx->mem.G();
+    if (S_bytes) *S_bytes = ctx->mem.S();
+    if (pool_total) *pool_total = ctx->mem.pool_total();
+    if (pool_free) *pool_free = ctx->mem.pool_free();
+    return 0;
+}
+
+int vattn_counters(vattn_ctx* ctx, int64_t* map_calls, int64_t* unmap_calls, double* map_us, double* unmap_us) {
+    if (!ctx) { set_error("counters: null context"); return -1; }
+    if (map_calls) *map_calls = ctx->mem.map_calls;
+    if (unmap_calls) *unmap_calls = ctx->mem.unmap_calls;
+    if (map_us) *map_us = ctx->mem.map_us;
+    if (unmap_us) *unmap_us = ctx->mem.unmap_us;
+    return 0;
+}
+
+int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new, const void* v_new,
+                    const int32_t* reqids, const int32_t* cu_q, const int64_t* kv_len_before, int n) {
+    if (!check_ctx_layer(ctx, layer, "append_kv")) return -1;
+    if (n < 0 || (n > 0 && (!k_new || !v_new || !reqids || !cu_q || !kv_len_before))) { set_error("append_kv: null argument"); return -1; }
+    if (n == 0) return 0;
+    if (cu_q[0] != 0) { set_error("append_kv: cu_q[0] must be 0"); return -1; }
+    for (int r = 0; r < n; ++r) {
+        const int64_t ql = static_cast<int64_t>(cu_q[r + 1]) - cu_q[r];
+        if (ql < 0) { set_error("append_kv: cu_q must be non-decreasing"); return -1; }
+        if (kv_len_before[r] < 0 || !check_request(ctx, reqids[r], kv_len_before[r] + ql, "append_kv")) return -1;
+    }
+    const size_t off_cu = align_up(sizeof(int32_t) * n, 8);
+    const size_t off_kv = align_up(off_cu + sizeof(int32_t) * (n + 1), 8);
+    const size_t bytes = off_kv + sizeof(int64_t) * n;
+    char *h, *d;
+    if (!ctx->ring.acquire(bytes, &h, &d)) return -1;
+    std::memcpy(h, reqids, sizeof(int32_t) * n);
+    std::memcpy(h + off_cu, cu_q, sizeof(int32_t) * (n + 1));
+    std::memcpy(h + off_kv, kv_len_before, sizeof(int64_t) * n);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!ctx->ring.commit(bytes, s)) return -1;
+    AppendArgs a{};
+    a.k_new = k_new; a.v_new = v_new;
+    a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1);
+    a.S = ctx->mem.S(); a.row_bytes = ctx->mem.T();
+    a.reqids = reinterpret_cast<const int32_t*>(d);
+    a.cu_q = reinterpret_cast<const int32_t*>(d + off_cu);
+    a.kv_before = reinterpret_cast<const int64_t*>(d + off_kv);
+    a.n = n; a.total_rows = cu_q[n];
+    return launch_append_kv(a, s) ? 0 : -1;
+}
+
+int64_t vattn_decode_workspace_bytes(vattn_ctx* ctx, const int64_t* kv_lens, int n) {
+    if (!ctx || n < 0 || (n > 0 && !kv_lens)) { set_error("decode_workspace_bytes: invalid argument"); return -1; }
+    // Sized for the smallest chunk the library may pick so that the answer does not depend on tuning.
+    int64_t chunks = 0;
+    const int min_chunk = ctx->decode_chunk > 0 ? ctx->decode_chunk : 64;
+    for (int i = 0; i < n; ++i) {
+        if (kv_lens[i] < 1) { set_error("decode_workspace_bytes: context lengths must be >= 1"); return -1; }
+        chunks += (kv_lens[i] + min_chunk - 1) / min_chunk;
+    }
+    const int64_t per_chunk = static_cast<int64_t>(ctx->cfg.num_q_heads) * (ctx->cfg.head_dim + 2) * 4;
+    return align_up(static_cast<size_t>(chunks * per_chunk), 256) + 256;
+}
+
+int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
+                      const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes) {
+    if (!check_ctx_layer(ctx, layer, "attn_decode")) return -1;
+    if (n < 0 || (n > 0 && (!q || !o || !reqids || !kv_lens || !workspace))) { set_error("attn_decode: null argument"); return -1; }
+    if (n == 0) return 0;
+    for (int r = 0; r < n; ++r) {
+        if (kv_lens[r] < 1) { set_error("attn_decode: context length must be >= 1"); return -1; }
+        if (!check_request(ctx, reqids[r], kv_lens[r], "attn_decode")) return -1;
+    }
+    const int chunk = choose_chunk(ctx, kv_lens, n);
+    const size_t off_kv = sizeof(int32_t) * n, off_cu = off_kv * 2;
+    const size_t bytes = off_cu + sizeof(int32_t) * (n + 1);
+    char *h, *d;
+    if (!ctx->ring.acquire(bytes, &h, &d)) return -1;
+    int32_t* h_req = reinterpret_cast<int32_t*>(h);
+    int32_t* h_kv = reinterpret_cast<int32_t*>(h + off_kv);
+    int32_t* h_cu = reinterpret_cast<int32_t*>(h + off_cu);
+    int64_t total = 0;
+    for (int r = 0; r < n; ++r) {
+        h_req[r] = reqids[r];
+        h_kv[r] = static_cast<int32_t>(kv_lens[r]);
+        h_cu[r] = static_cast<int32_t>(total);
+        total += (kv_lens[r] + chunk - 1) / chunk;
+    }
+    h_cu[n] = static_cast<int32_t>(total);
+    const int Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
+    const size_t part_o_bytes = align_up(static_cast<size_t>(total) * Hq * D * 4, 256);
+    const size_t need = part_o_bytes + static_cast<size_t>(total) * Hq * 2 * 4;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) { set_error("attn_decode: workspace must be 256-byte aligned"); return -1; }
+    if (workspace_bytes < need) { set_error("attn_decode: workspace too small (" + std::to_string(workspace_bytes) + " < " + std::to_string(need) + ")"); return -1; }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!ctx->ring.commit(bytes, s)) return -1;
+
+    DecodeArgs a{};
+    a.q = q; a.o = o;
+    a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1); a.S = ctx->mem.S();
+    a.Hq = Hq; a.H = ctx->cfg.num_kv_heads; a.D = D;
+    a.reqids = reinterpret_cast<const int32_t*>(d);
+    a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
+    a.cu_chunks = reinterpret_cast<const int32_t*>(d + off_cu);
+    a.n = n; a.total_chunks = static_cast<int>(total); a.chunk_tokens = chunk; a.scale = scale;
+    a.part_o = static_cast<float*>(workspace);
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + part_o_bytes);
+    if (ctx->timing && !ctx->timers[0].begin(s)) return -1;
+    if (!launch_decode_splitk(a, s)) return -1;
+    if (ctx->timing && !ctx->timers[0].end(s)) return -1;
+    if (ctx->timing && !ctx->timers[2].begin(s)) return -1;
+    if (!launch_decode_reduce(a, s)) return -1;
+    if (ctx->timing && !ctx->timers[2].end(s)) return -1;
+    return 0;
+}
+
+int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
+                       const int32_t* cu_q, const int64_t* kv_lens, int n, float scale) {
+    if (!check_ctx_layer(ctx, layer, "attn_prefill")) return -1;
+    if (n < 0 || (n > 0 && (!q || !o || !reqids || !cu_q || !kv_lens))) { set_error("attn_prefill: null argument"); return -1; }
+    if (n == 0) return 0;
+    if (cu_q[0] != 0) { set_error("attn_prefill: cu_q[0] must be 0"); return -1; }
+    const int H = ctx->cfg.num_kv_heads, Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
+    const int BM = prefill_tile_rows(Hq, H, D);
+    for (int r = 0; r < n; ++r) {
+        const int64_t ql = static_cast<int64_t>(cu_q[r + 1]) - cu_q[r];
+        if (ql < 0) { set_error("attn_prefill: cu_q must be non-decreasing"); return -1; }
+        if (kv_lens[r] < ql) { set_error("attn_prefill: kv_len < q_len for batch slot " + std::to_string(r)); return -1; }
+        if (ql > 0 && !check_request(ctx, reqids[r], kv_lens[r], "attn_prefill")) return -1;
+    }
+    // One queue per XCD.  Workgroup ids are dealt to the 8 XCDs round-robin, so giving XCD x the
+    // streams (request, KV head, tile class) with index == x (mod 8) keeps all readers of one K/V
+    // stream behind the same L2.  KV heads are split into tile classes when there are fewer than 8.
+    const int nsplit = H < 8 ? (8 + H - 1) / H : 1;
+    struct Cost { PrefillItem it; int64_t cost; };
+    std::vector<Cost> queues[8];
+    for (int r = 0; r < n; ++r) {
+        const int ql = cu_q[r + 1] - cu_q[r];
+        const int tiles = (ql + BM - 1) / BM;
+        const int64_t off = kv_lens[r] - ql;
+        for (int t = 0; t < tiles; ++t) {
+            const int64_t visible = std::min<int64_t>(static_cast<int64_t>(t + 1) * BM, ql) + off;
+            for (int kvh = 0; kvh < H; ++kvh) {
+                const int x = (kvh * nsplit + t % nsplit + ((H * nsplit) % 8 ? r : 0)) & 7;
+                queues[x].push_back(Cost{PrefillItem{r, kvh, t, 0}, visible});
+            }
+        }
+    }
+    size_t per_xcd = 0;
+    for (auto& qx : queues) {
+        std::stable_sort(qx.begin(), qx.end(), [](const Cost& x, const Cost& y) { return x.cost > y.cost; });
+        per_xcd = std::max(per_xcd, qx.size());
+    }
+    if (per_xcd == 0) return 0;
+    const size_t off_cu = sizeof(int32_t) * n;
+    const size_t off_kv = off_cu + sizeof(int32_t) * (n + 1);
+    const size_t off_items = align_up(off_kv + sizeof(int32_t) * n, 16);
+    const size_t bytes = off_items + sizeof(PrefillItem) * per_xcd * 8;
+    char *h, *d;
+    if (!ctx->ring.acquire(bytes, &h, &d)) return -1;
+    std::memcpy(h, reqids, sizeof(int32_t) * n);
+    std::memcpy(h + off_cu, cu_q, sizeof(int32_t) * (n + 1));
+    int32_t* h_kv = reinterpret_cast<int32_t*>(h + off_kv);
+    for (int r = 0; r < n; ++r) h_kv[r] = static_cast<int32_t>(kv_lens[r]);
+    PrefillItem* h_items = reinterpret_cast<PrefillItem*>(h + off_items);
+    for (int x = 0; x < 8; ++x)
+        for (size_t j = 0; j < per_xcd; ++j)
+            h_items[x * per_xcd + j] = j < queues[x].size() ? queues[x][j].it : PrefillItem{-1, 0, 0, 0};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!ctx->ring.commit(bytes, s)) return -1;
+
+    PrefillArgs a{};
+    a.q = q; a.o = o;
+    a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1); a.S = ctx->mem.S();
+    a.Hq = Hq; a.H = H; a.D = D;
+    a.reqids = reinterpret_cast<const int32_t*>(d);
+    a.cu_q = reinterpret_cast<const int32_t*>(d + off_cu);
+    a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
+    a.items = reinterpret_cast<const PrefillItem*>(d + off_items);
+    a.items_per_xcd = static_cast<int>(per_xcd); a.n = n; a.scale = scale;
+    if (ctx->timing && !ctx->timers[1].begin(s)) return -1;
+    if (!launch_prefill(a, s)) return -1;
+    if (ctx->timing && !ctx->timers[1].end(s)) return -1;
+    return 0;
+}
+
+int vattn_set_timing(vattn_ctx* ctx, int enabled) {
+    if (!ctx) { set_error("set_timing: null context"); return -1; }
+    ctx->timing = enabled != 0;
+    return 0;
+}
+
+int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* launches) {
+    if (!ctx || which < 0 || which > 2) { set_error("kernel_time: invalid argument"); return -1; }
+    return ctx->timers[which].collect(total_ms, launches) ? 0 : -1;
+}
+
+int vattn_set_decode_chunk(vattn_ctx* ctx, int tokens) {
+    if (!ctx || tokens < 0 || tokens % 32 != 0) { set_error("set_decode_chunk: tokens must be a non-negative multiple of 32"); return -1; }
+    ctx->decode_chunk = tokens;
+    return 0;
+}
+
+}  // extern "C"

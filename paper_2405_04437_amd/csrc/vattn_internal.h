@@ -1,0 +1,140 @@
+// Internal declarations shared by the translation units of libvattn (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/vattn.h"
+
+namespace vattn {
+
+void set_error(const std::string& msg);
+bool hip_ok(hipError_t e, const char* what);  // records the error text and returns false on failure
+
+// ---------------------------------------------------------------------------------------------
+// Memory manager: 2N virtual reservations, a pool of physical page-group handles, per-reqId counts.
+// Follows Sec. 5 of the paper (virtual tensors, reqId indexing, init/alloc_reqid/free_reqid/step).
+// ---------------------------------------------------------------------------------------------
+class KvMemory {
+public:
+    ~KvMemory();
+    bool init(const vattn_config& cfg);
+    int alloc_reqid();
+    int free_reqid(int reqid);
+    int step(const int64_t* seq_lens, int count);
+
+    char* sub_tensor(int layer, int which, int reqid) const {
+        return base_[static_cast<size_t>(layer) * 2 + which] + static_cast<int64_t>(reqid) * S_;
+    }
+    char* buffer_base(int layer, int which) const { return base_[static_cast<size_t>(layer) * 2 + which]; }
+    bool valid_reqid(int r) const { return r >= 0 && r < B_; }
+    bool is_active(int r) const { return active_[r] != 0; }
+    int64_t mapped(int r) const { return mapped_[r]; }
+    int64_t mapped_tokens(int r) const { return mapped_[r] * G_ / T_; }
+    int64_t G() const { return G_; }
+    int64_t S() const { return S_; }
+    int64_t T() const { return T_; }
+    int64_t pool_total() const { return pool_total_; }
+    int64_t pool_free() const { return static_cast<int64_t>(free_handles_.size()); }
+    int64_t map_calls = 0, unmap_calls = 0;
+    double map_us = 0, unmap_us = 0;
+
+private:
+    bool map_rows(int r, int64_t from, int64_t to);  // page-group rows [from,to) of reqId r, all buffers
+    void unmap_rows(int r, int64_t keep);            // unmap rows [keep, mapped) and return handles
+    int N_ = 0, B_ = 0, device_ = 0;
+    uint32_t policy_ = 0;
+    int64_t L_ = 0, G_ = 0, S_ = 0, T_ = 0, pool_total_ = 0;
+    std::vector<char*> base_;                                     // 2N reservations of B*S bytes
+    std::vector<hipMemGenericAllocationHandle_t> free_handles_;   // created, unmapped
+    std::vector<std::vector<hipMemGenericAllocationHandle_t>> held_;  // per reqId: rows x 2N handles
+    std::vector<uint8_t> active_;
+    std::vector<int64_t> mapped_;
+    hipMemAccessDesc access_{};
+};
+
+// ---------------------------------------------------------------------------------------------
+// Pinned staging ring for the small index arrays every attention call uploads.
+// ---------------------------------------------------------------------------------------------
+class MetaRing {
+public:
+    ~MetaRing();
+    // Returns a host pointer (pinned) of at least `bytes` bytes and its device mirror.
+    bool acquire(size_t bytes, char** host, char** dev);
+    // Enqueues the upload of the first `bytes` bytes of the acquired slot on `stream`.
+    bool commit(size_t bytes, hipStream_t stream);
+
+private:
+    static constexpr int kSlots = 8;
+    bool grow(size_t bytes);
+    char* host_ = nullptr;
+    char* dev_ = nullptr;
+    size_t slot_bytes_ = 0;
+    int cur_ = -1;
+    hipEvent_t ev_[kSlots] = {};
+    bool pending_[kSlots] = {};
+};
+
+struct KernelTimer {
+    struct Pair { hipEvent_t a, b; };
+    std::vector<Pair> open;    // recorded, not yet read
+    std::vector<Pair> spare;   // reusable events
+    bool begin(hipStream_t s);
+    bool end(hipStream_t s);
+    bool collect(double* total_ms, int64_t* launches);
+    void destroy();
+};
+
+// ---------------------------------------------------------------------------------------------
+// Kernel launchers (one per .hip file).  All pointers are device pointers.
+// ---------------------------------------------------------------------------------------------
+struct AppendArgs {
+    const void* k_new; const void* v_new;   // [rows, H, D] bf16
+    char* k_base; char* v_base;             // buffer bases of the layer
+    int64_t S;                              // bytes between consecutive reqIds
+    int64_t row_bytes;                      // H*D*P
+    const int32_t* reqids; const int32_t* cu_q; const int64_t* kv_before;  // device, n / n+1 / n
+    int n; int total_rows;
+};
+bool launch_append_kv(const AppendArgs& a, hipStream_t stream);
+
+struct DecodeArgs {
+    const void* q; void* o;                 // [n, Hq, D] bf16
+    const char* k_base; const char* v_base; int64_t S;
+    int Hq, H, D;
+    const int32_t* reqids; const int32_t* kv_lens; const int32_t* cu_chunks;  // device: n, n, n+1
+    int n; int total_chunks; int chunk_tokens;
+    float scale;
+    float* part_o;   // [total_chunks, Hq, D] un-normalised partial outputs
+    float* part_ml;  // [total_chunks, Hq, 2] running max (log2 domain) and partial sum
+};
+bool launch_decode_splitk(const DecodeArgs& a, hipStream_t stream);
+bool launch_decode_reduce(const DecodeArgs& a, hipStream_t stream);
+
+struct PrefillItem { int32_t req; int32_t kvh; int32_t q_tile; int32_t pad; };
+struct PrefillArgs {
+    const void* q; void* o;                 // [sum q_len, Hq, D] bf16
+    const char* k_base; const char* v_base; int64_t S;
+    int Hq, H, D;
+    const int32_t* reqids; const int32_t* cu_q; const int32_t* kv_lens;   // device
+    const PrefillItem* items;               // device: 8 queues of items_per_xcd entries each
+    int items_per_xcd; int n;
+    float scale;
+};
+int prefill_tile_rows(int Hq, int H, int D);     // query positions covered by one work item
+int prefill_heads_per_item(int Hq, int H, int D);
+bool launch_prefill(const PrefillArgs& a, hipStream_t stream);
+
+}  // namespace vattn
+
+struct vattn_ctx {
+    vattn_config cfg{};
+    vattn::KvMemory mem;
+    vattn::MetaRing ring;
+    vattn::KernelTimer timers[3];
+    bool timing = false;
+    int decode_chunk = 0;
+};

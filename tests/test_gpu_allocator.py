@@ -1,0 +1,142 @@
+"""GPU parity of the memory manager against the integer model: bit-exact mapped page counts and
+offsets per reqId after every call, and the mapped ranges really are readable and writable."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle.allocator import AllocatorModel
+
+pytestmark = pytest.mark.gpu
+KiB, MiB = 1024, 1024 * 1024
+
+
+def _hip():
+    return ctypes.CDLL("libamdhip64.so")
+
+
+def _compare(lib_ctx, model, B):
+    assert lib_ctx.stats() == model.stats()
+    for r in range(B):
+        assert lib_ctx.query(r) == model.query(r), f"reqId {r}"
+
+
+@pytest.mark.parametrize("policy", ["sync", "deferred"])
+@pytest.mark.parametrize("G", [64 * KiB, 2 * MiB])
+def test_algorithm1_trace_matches_model_bit_exactly(policy, G):
+    import paper_2405_04437_amd as P
+
+    sh = W.YI_6B
+    N, B, L = 2, 12, 6000
+    pool = 220 if G == 64 * KiB else 40
+    pol = P.POLICY_DEFERRED if policy == "deferred" else P.POLICY_SYNC_UNMAP
+    va = P.Vattn(N, B, L, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, pool * G, G, policy=pol)
+    model = AllocatorModel(N, B, L, sh.num_kv_heads, sh.head_dim, 2, G, pool, policy)
+    _compare(va, model, B)
+    # Algorithm 1 over a seeded arrival trace; the pool is small enough that step() sometimes fails
+    events = W.serving_trace(seed=77, max_batch=B, iterations=120, prompt_range=(1, 3000), out_range=(1, 60))
+    lens = [0] * B
+    remaining = {}
+    waiting = []
+    failures = 0
+    for kind, prompt, out in events:
+        if kind == "arrive":
+            waiting.append((prompt, out))
+            continue
+        while waiting:
+            a, b = va.alloc_reqid(), model.alloc_reqid()
+            assert a == b
+            if a < 0:
+                break
+            p, o = waiting.pop(0)
+            lens[a] = p
+            remaining[a] = o
+        ra, rb = va.step(lens), model.step(lens)
+        assert ra == rb
+        _compare(va, model, B)
+        if ra != 0:  # preempt the longest request, as a framework would
+            failures += 1
+            victim = max(remaining, key=lambda r: lens[r])
+            lens[victim] = 0
+            del remaining[victim]
+            assert va.free_reqid(victim) == model.free_reqid(victim) == 0
+            _compare(va, model, B)
+            continue
+        for r in list(remaining):
+            remaining[r] -= 1
+            if remaining[r] <= 0 or lens[r] >= L:
+                lens[r] = 0
+                del remaining[r]
+                assert va.free_reqid(r) == model.free_reqid(r) == 0
+            else:
+                lens[r] += 1
+        _compare(va, model, B)
+    assert failures > 0, "the trace should exercise the failure path"
+    mc, uc, _, _ = va.counters()
+    assert (mc, uc) == (model.map_calls, model.unmap_calls)
+    va.destroy()
+
+
+def test_invalid_arguments_match_model():
+    import paper_2405_04437_amd as P
+
+    va = P.Vattn(1, 3, 1000, 8, 2, 64, 8 * 64 * KiB, 64 * KiB)
+    model = AllocatorModel(1, 3, 1000, 2, 64, 2, 64 * KiB, 8)
+    for seq in ([1, 0, 0], [0, 0], [0, 0, 0, 0]):
+        assert va.step(seq) == model.step(seq)
+    a = va.alloc_reqid(); assert a == model.alloc_reqid()
+    for seq in ([1001, 0, 0], [5, 1, 0], [-1, 0, 0], [1000, 0, 0]):
+        assert va.step(seq) == model.step(seq), seq
+        assert va.query(0) == model.query(0)
+    assert va.free_reqid(2) == model.free_reqid(2) == -1
+    assert va.free_reqid(5) == model.free_reqid(5) == -1
+    assert va.kv_ptr(0, 0, 3) == 0 and va.kv_ptr(1, 0, 0) == 0 and va.kv_ptr(0, 2, 0) == 0
+    va.destroy()
+    with pytest.raises(P.VattnError):
+        P.Vattn(1, 3, 1000, 8, 2, 64, 1 << 20, 5000)       # not a multiple of the granularity
+    with pytest.raises(P.VattnError):
+        P.Vattn(1, 3, 1000, 8, 3, 64, 1 << 20)             # Hq % H != 0
+    with pytest.raises(P.VattnError):
+        P.Vattn(1, 3, 1000, 8, 2, 96, 1 << 20)             # unsupported head dim
+
+
+def test_mapped_ranges_hold_data_across_growth_and_reuse():
+    """Bytes written through the contiguous sub-tensor survive later growth (new pages appended
+    behind them), sub-tensors of different reqIds are disjoint, and offsets are reqId*S."""
+    import paper_2405_04437_amd as P
+
+    hip = _hip()
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    G = 64 * KiB
+    va = P.Vattn(2, 4, 4096, 8, 2, 64, 64 * G, G)
+    T = 2 * 64 * 2
+    _, S, _, _ = va.stats()
+    a, b = va.alloc_reqid(), va.alloc_reqid()
+    assert va.step([300, 100, 0, 0]) == 0
+    base = va.kv_ptr(0, 0, 0)
+    for layer in range(2):
+        for which in range(2):
+            for r in (a, b):
+                assert va.kv_ptr(layer, which, r) - va.kv_ptr(layer, which, 0) == r * S
+    rng = np.random.default_rng(1)
+    blobs = {}
+    for layer in range(2):
+        for which in range(2):
+            for r, n in ((a, 300), (b, 100)):
+                data = rng.integers(0, 256, size=n * T, dtype=np.uint8)
+                blobs[(layer, which, r)] = data
+                assert hip.hipMemcpy(va.kv_ptr(layer, which, r), data.ctypes.data, data.nbytes, 1) == 0
+    assert va.step([3000, 100, 0, 0]) == 0          # a grows by many page-groups
+    assert va.query(a)[1] == -(-3000 * T // G)
+    tail = rng.integers(0, 256, size=(3000 - 300) * T, dtype=np.uint8)
+    assert hip.hipMemcpy(va.kv_ptr(1, 1, a) + 300 * T, tail.ctypes.data, tail.nbytes, 1) == 0
+    for key, data in blobs.items():
+        back = np.empty_like(data)
+        assert hip.hipMemcpy(back.ctypes.data, va.kv_ptr(*key), data.nbytes, 2) == 0
+        assert np.array_equal(back, data), key
+    back = np.empty_like(tail)
+    assert hip.hipMemcpy(back.ctypes.data, va.kv_ptr(1, 1, a) + 300 * T, tail.nbytes, 2) == 0
+    assert np.array_equal(back, tail)
+    assert base == va.kv_ptr(0, 0, 0)
+    va.destroy()

@@ -1,0 +1,186 @@
+"""GPU parity of the HIP attention path against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import attention as OA
+from parity import check
+
+pytestmark = pytest.mark.gpu
+KiB, MiB = 1024, 1024 * 1024
+
+
+def _session(shape, n, max_ctx, G=2 * MiB, layers=1, policy=0, slack=2):
+    from paper_2405_04437_amd.runtime import KvSession
+
+    per_req = (max_ctx * shape.token_bytes + G - 1) // G * G
+    budget = per_req * 2 * layers * (n + slack)
+    return KvSession(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, n + slack, max_ctx, budget, layers, G, policy)
+
+
+def _run_decode(shape, kv_lens, seed, G=2 * MiB, chunk=0):
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
+
+    n = len(kv_lens)
+    inp = W.draw_attention_inputs(shape, [1] * n, kv_lens, seed)
+    scale = W.softmax_scale(shape.head_dim)
+    s = _session(shape, n, max(kv_lens), G)
+    reqids = s.load_contexts(inp.k, inp.v)
+    if chunk:
+        assert s.va.set_decode_chunk(chunk) == 0
+    got = tensor_to_f32(s.decode(0, bits_to_tensor(inp.q), reqids, kv_lens, scale))
+    s.close()
+    want = OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale)
+    return got, want, inp
+
+
+def test_config1_tiny_decode_matches_oracle():
+    wl = W.config(0)
+    got, want, _ = _run_decode(wl.shape, wl.kv_lens, wl.seed)
+    check(got, want, "C1 decode")
+
+
+@pytest.mark.parametrize("Hq,H,D", [(8, 2, 64), (32, 4, 128), (56, 8, 128), (4, 4, 128), (40, 2, 64), (7, 1, 128)])
+def test_decode_shapes_ragged_lengths(Hq, H, D):
+    shape = W.Shape("t", Hq, H, D, 1)
+    kv_lens = [1, 2, 31, 32, 33, 63, 64, 65, 511, 512, 513, 1000, 2049]
+    got, want, _ = _run_decode(shape, kv_lens, seed=Hq * 31 + D)
+    check(got, want, f"decode Hq={Hq} H={H} D={D}")
+
+
+@pytest.mark.parametrize("chunk", [32, 64, 256, 512, 4096])
+def test_decode_invariant_to_chunk_size(chunk):
+    shape = W.YI_6B
+    kv_lens = [777, 3000, 1, 4097]
+    got, want, _ = _run_decode(shape, kv_lens, seed=5, chunk=chunk)
+    check(got, want, f"decode chunk={chunk}")
+
+
+@pytest.mark.parametrize("G", [4 * KiB, 64 * KiB, 2 * MiB])
+def test_decode_invariant_to_page_group_size(G):
+    shape = W.LLAMA3_8B
+    kv_lens = [1500, 37, 2600]
+    got, want, _ = _run_decode(shape, kv_lens, seed=6, G=G)
+    check(got, want, f"decode G={G}")
+
+
+def test_context_of_one_returns_v_bit_exactly():
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_bits
+
+    shape = W.YI_34B
+    inp = W.draw_attention_inputs(shape, [1, 1], [1, 1], seed=9)
+    s = _session(shape, 2, 16)
+    reqids = s.load_contexts(inp.k, inp.v)
+    o = tensor_to_bits(s.decode(0, bits_to_tensor(inp.q), reqids, [1, 1], 0.0884))
+    p = tensor_to_bits(s.prefill(0, bits_to_tensor(inp.q), reqids, [0, 1, 2], [1, 1], 0.0884))
+    s.close()
+    for r in range(2):
+        for h in range(shape.num_q_heads):
+            assert np.array_equal(o[r, h], inp.v[r][0, h // shape.group])
+            assert np.array_equal(p[r, h], inp.v[r][0, h // shape.group])
+
+
+def _run_prefill(shape, q_lens, kv_lens, seed, G=2 * MiB):
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
+
+    inp = W.draw_attention_inputs(shape, q_lens, kv_lens, seed)
+    scale = W.softmax_scale(shape.head_dim)
+    s = _session(shape, len(q_lens), max(kv_lens), G)
+    reqids = s.load_contexts(inp.k, inp.v)
+    got = tensor_to_f32(s.prefill(0, bits_to_tensor(inp.q), reqids, inp.cu_q, kv_lens, scale))
+    s.close()
+    want = OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale)
+    return got, want
+
+
+@pytest.mark.parametrize("Hq,H,D", [(8, 2, 64), (32, 8, 128), (14, 2, 128), (4, 4, 64), (3, 3, 128)])
+def test_prefill_shapes_ragged_lengths(Hq, H, D):
+    shape = W.Shape("t", Hq, H, D, 1)
+    q_lens = [1, 5, 64, 127, 128, 129, 300, 0, 513]
+    got, want = _run_prefill(shape, q_lens, list(q_lens[:7]) + [10, 513], seed=Hq + D)
+    check(got, want, f"prefill Hq={Hq} H={H} D={D}")
+
+
+def test_prefill_chunk_appended_to_existing_context():
+    """A 300-token chunk appended at context 1000 attends to all 1300 tokens (config 4's shape of
+    request, scaled down), together with fresh prompts and a decode-like q_len=1 row."""
+    shape = W.YI_34B
+    got, want = _run_prefill(shape, [300, 200, 1, 77], [1300, 200, 555, 400], seed=12)
+    check(got, want, "chunked prefill")
+
+
+def test_decode_equals_last_prefill_row_on_gpu():
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
+
+    shape = W.LLAMA3_8B
+    L = 700
+    inp = W.draw_attention_inputs(shape, [L], [L], seed=13)
+    scale = W.softmax_scale(128)
+    s = _session(shape, 1, L)
+    reqids = s.load_contexts(inp.k, inp.v)
+    q = bits_to_tensor(inp.q)
+    pre = tensor_to_f32(s.prefill(0, q, reqids, [0, L], [L], scale))
+    dec = tensor_to_f32(s.decode(0, q[L - 1:L].contiguous(), reqids, [L], scale))
+    s.close()
+    want = OA.attention_request(inp.q, inp.k[0], inp.v[0], scale, rows=np.array([L - 1], dtype=np.int32))
+    check(dec[0], want[0], "decode row")
+    check(pre[L - 1], want[0], "prefill last row")
+
+
+def test_batch_slots_map_to_arbitrary_reqids_with_holes():
+    """Continuous batching: after a request in the middle leaves, the remaining batch slots keep
+    their reqIds (holes in the virtual tensors) and a newcomer reuses the freed id."""
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
+
+    shape = W.YI_6B
+    kv = [400, 90, 1000, 257]
+    inp = W.draw_attention_inputs(shape, [1] * 4, kv, seed=14)
+    scale = W.softmax_scale(128)
+    s = _session(shape, 4, 1024)
+    ids = s.load_contexts(inp.k, inp.v)
+    s.finish(ids[1])
+    new = W.draw_attention_inputs(shape, [1], [333], seed=15)
+    nid = s.load_contexts(new.k, new.v)[0]
+    assert nid == ids[1]
+    order = [3, 0, 1, 2]  # batch slot -> which request; slot 2 is the newcomer
+    reqids = [ids[3], ids[0], nid, ids[2]]
+    q_bits = np.stack([inp.q[3], inp.q[0], new.q[0], inp.q[2]])
+    lens = [kv[3], kv[0], 333, kv[2]]
+    got = tensor_to_f32(s.decode(0, bits_to_tensor(q_bits), reqids, lens, scale))
+    s.close()
+    ks = [inp.k[3], inp.k[0], new.k[0], inp.k[2]]
+    vs = [inp.v[3], inp.v[0], new.v[0], inp.v[2]]
+    want = OA.attention_batch(q_bits, np.arange(5), ks, vs, scale)
+    check(got, want, "holes")
+
+
+def test_attention_rejects_unbacked_or_inactive_requests():
+    import torch
+    import paper_2405_04437_amd as P
+    from paper_2405_04437_amd.runtime import bits_to_tensor
+
+    shape = W.TINY
+    s = _session(shape, 2, 4096, G=64 * KiB)
+    inp = W.draw_attention_inputs(shape, [1], [100], seed=16)
+    ids = s.load_contexts(inp.k, inp.v)
+    q = bits_to_tensor(inp.q)
+    o = torch.empty_like(q)
+    ws = s.workspace([4096])
+    tokens_backed = 64 * KiB // shape.token_bytes
+    assert s.va.attn_decode(0, s.stream, q, o, ids, [tokens_backed + 1], 0.1, ws, ws.numel()) == -1
+    assert "mapped" in P.last_error()
+    assert s.va.attn_decode(0, s.stream, q, o, [1], [10], 0.1, ws, ws.numel()) == -1      # inactive id
+    assert s.va.attn_decode(0, s.stream, q, o, ids, [0], 0.1, ws, ws.numel()) == -1       # empty context
+    assert s.va.attn_decode(0, s.stream, q, o, ids, [100], 0.1, ws, 16) == -1             # workspace
+    assert s.va.attn_prefill(0, s.stream, q, o, ids, [0, 1], [0], 0.1) == -1              # kv_len < q_len
+    assert s.va.attn_prefill(1, s.stream, q, o, ids, [0, 1], [100], 0.1) == -1            # layer
+    assert s.va.attn_decode(0, s.stream, q, o, ids, [100], 0.1, ws, ws.numel()) == 0
+    s.close()
+
+
+def test_config2_yi6b_decode_full_size_matches_oracle():
+    """BASELINE config 2 at full size, in the launch configuration bench.py times (default chunking,
+    2 MiB page-groups): every output row checked against the oracle."""
+    wl = W.config(1)
+    got, want, _ = _run_decode(wl.shape, wl.kv_lens, wl.seed)
+    check(got, want, "C2 decode")
