@@ -1,0 +1,323 @@
+#!/usr/bin/env python3
+"""Benchmark of the contiguous-KV attention hot path on one MI355X.
+
+Headline workload (N=1): BASELINE config 2, "Yi-6B-shaped decode" - 64 requests, 32 query heads,
+4 KV heads, head_dim 128, bf16, contexts U[1024,16384]; every step each request grows by one token:
+    step()  ->  append_kv (new K/V rows, all layers)  ->  attn_decode (split-K + reduce) on one layer
+i.e. one pass over all rows of the hot path.  Layers are rotated so consecutive steps read different
+KV buffers.  `value` is algorithmic KV bytes moved per second over the whole step (inputs resident in
+HBM); `roofline` prices the dominant kernel (split-K decode) alone, timed with HIP events the library
+records around every launch on the launch stream.
+
+The line also carries `also`: prefill (config 3) TFLOP/s, the mixed step of config 4 and the
+long-context request of config 5, each with its own roofline fraction, and `cpu_baseline`: the CPU
+oracle timed on the same decode batch.
+
+Synthetic data: N(0,1) bf16 Q/K/V drawn on the device from a seeded generator; context lengths from
+workloads.config().  Nothing is read from disk except the optional measured-traffic file under
+profiles/ (rocprofv3 counter results for the same command).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+MiB = 1024 * 1024
+
+
+def _decode_bytes(shape, kv_lens):
+    """Algorithmic bytes of one decode layer-step: every K and V byte once, Q read, O written."""
+    per_tok = 2 * shape.num_kv_heads * shape.head_dim * 2
+    qo = 2 * shape.num_q_heads * shape.head_dim * 2
+    return sum(int(L) * per_tok + qo for L in kv_lens)
+
+
+def _prefill_flops(shape, q_lens, kv_lens):
+    """Causal-only flops: 4*Hq*D per (query row, visible key) pair."""
+    tot = 0
+    for ql, kl in zip(q_lens, kv_lens):
+        off = kl - ql
+        tot += ql * off + ql * (ql + 1) // 2
+    return 4 * shape.num_q_heads * shape.head_dim * tot
+
+
+def _fill_contexts(sess, torch, gen, shape, kv_lens, layers, keep_host=False):
+    """Admit the requests, back them with step() and write N(0,1) K/V through append_kv."""
+    ids = [sess.admit(int(L)) for L in kv_lens]
+    sess.step()
+    host = []
+    for r, L in zip(ids, kv_lens):
+        done = 0
+        ks, vs = [], []
+        while done < L:
+            n = min(8192, L - done)
+            k = torch.randn((n, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+            v = torch.randn((n, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+            for layer in range(layers):
+                sess.append(layer, k, v, [r], [0, n], [done])
+            if keep_host:
+                ks.append(k.cpu()); vs.append(v.cpu())
+            done += n
+        if keep_host:
+            host.append((torch.cat(ks), torch.cat(vs)))
+    torch.cuda.synchronize()
+    return ids, host
+
+
+def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, churn=False):
+    from paper_2405_04437_amd import POLICY_DEFERRED
+    from paper_2405_04437_amd.runtime import KvSession, tensor_to_bits, tensor_to_f32
+
+    shape = wl.shape
+    n = sum(1 for q in wl.q_lens if q == 1)
+    kv_lens = [int(x) for x in wl.kv_lens[:n]]
+    total_steps = steps + warmup + 2
+    ctx_hi = wl.extra["ctx_range"][1] if churn else 0
+    max_ctx = max(max(kv_lens), ctx_hi) + total_steps + 8
+    G = 2 * MiB
+    headroom = n // 4 + 4
+    per_req = (max_ctx * shape.token_bytes + G - 1) // G * G
+    budget = per_req * 2 * layers * (n + headroom)
+    sess = KvSession(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, n + headroom, max_ctx, budget, layers, G,
+                     POLICY_DEFERRED)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(wl.seed)
+    ids, host = _fill_contexts(sess, torch, gen, shape, kv_lens, layers, keep_host=with_oracle)
+    scale = W.softmax_scale(shape.head_dim)
+    q = torch.randn((n, shape.num_q_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    knew = torch.randn((n, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    vnew = torch.randn((n, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    o = torch.empty_like(q)
+    lens = list(kv_lens)
+    ws = sess.workspace([max(L, ctx_hi) + total_steps for L in lens])
+    if churn:  # source rows for the K/V of newly arriving requests (their prefill's KV write)
+        kbig = torch.randn((ctx_hi, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        vbig = torch.randn((ctx_hi, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    cu = list(range(n + 1))
+    rng = __import__("numpy").random.default_rng(wl.seed)
+
+    def one_step(i):
+        nonlocal lens, ids
+        if churn:  # config 4: ~10% of the requests finish and as many arrive, reusing backed reqIds
+            k = max(1, int(round(0.10 * n)))
+            arrivals = []
+            for slot in rng.choice(n, size=k, replace=False):
+                sess.finish(ids[slot])
+                lens[slot] = int(rng.integers(wl.extra["ctx_range"][0], wl.extra["ctx_range"][1], endpoint=True))
+                ids[slot] = sess.admit(lens[slot])
+                arrivals.append(slot)
+            sess.step()
+            for slot in arrivals:  # the newcomer's context is written in place (contiguous copy)
+                for layer in range(layers):
+                    sess.append(layer, kbig[:lens[slot]], vbig[:lens[slot]], [ids[slot]], [0, lens[slot]], [0])
+        before = list(lens)
+        for r, L in zip(ids, lens):
+            sess.seq_lens[r] = L + 1
+        sess.step()
+        for layer in range(layers):
+            sess.append(layer, knew, vnew, ids, cu, before)
+        lens = [L + 1 for L in lens]
+        sess.decode(i % layers, q, ids, lens, scale, out=o, ws=ws)
+
+    for i in range(warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    sess.va.set_timing(True)
+    sess.va.kernel_time(0); sess.va.kernel_time(2)
+    map0 = sess.va.counters()
+    bytes_total = 0
+    t0 = time.perf_counter()
+    for i in range(steps):
+        one_step(warmup + i)
+        bytes_total += _decode_bytes(shape, lens)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    k_ms, k_n = sess.va.kernel_time(0)
+    r_ms, r_n = sess.va.kernel_time(2)
+    sess.va.set_timing(False)
+    map1 = sess.va.counters()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    bytes_per_step = bytes_total / steps
+    res = {
+        "ms_per_step": ms_per_step,
+        "gbs_step": bytes_per_step / (ms_per_step * 1e6),
+        "kernel_ms": k_ms / max(k_n, 1),
+        "reduce_ms": r_ms / max(r_n, 1),
+        "gbs_kernel": bytes_per_step / (k_ms / max(k_n, 1) * 1e6),
+        "bytes_per_step": bytes_per_step,
+        "tokens_in_batch": sum(lens),
+        "map_calls_in_timed_region": map1[0] - map0[0],
+        "map_us_in_timed_region": map1[2] - map0[2],
+        "unmap_calls_in_timed_region": map1[1] - map0[1],
+    }
+    if with_oracle and not churn:
+        # CPU oracle on the same batch as the last timed step (layer = last used layer).
+        import numpy as np
+        from oracle import attention as OA
+
+        last_layer = (warmup + steps - 1) % layers
+        torch.cuda.synchronize()
+        qb = tensor_to_bits(q)
+        kb_new, vb_new = tensor_to_bits(knew), tensor_to_bits(vnew)
+        ks, vs = [], []
+        grown = lens[0] - kv_lens[0]
+        for r in range(n):
+            k0, v0 = host[r]
+            ks.append(np.concatenate([tensor_to_bits(k0)] + [kb_new[r:r + 1]] * grown))
+            vs.append(np.concatenate([tensor_to_bits(v0)] + [vb_new[r:r + 1]] * grown))
+        t0 = time.perf_counter()
+        want = OA.attention_batch(qb, np.arange(n + 1), ks, vs, scale)
+        dt = time.perf_counter() - t0
+        got = tensor_to_f32(o)
+        err = float(np.abs(got - want).max())
+        rel = float((np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max())
+        res["cpu_baseline"] = {
+            "value": _decode_bytes(shape, lens) / dt / 1e9, "unit": "GB/s", "cores": OA.num_threads(), "kind": "oracle",
+            "sample": f"the full decode batch of the last timed step once ({n} requests, {sum(lens)} tokens, layer {last_layer}): {dt:.2f} s",
+            "gpu_vs_oracle_max_abs": err, "gpu_vs_oracle_row_rel": rel,
+        }
+    sess.close()
+    return res
+
+
+def run_prefill(args, torch, W, wl, iters, warmup, req_filter=None):
+    from paper_2405_04437_amd.runtime import KvSession
+
+    shape = wl.shape
+    idx = [i for i, ql in enumerate(wl.q_lens) if ql > 1] if req_filter is None else req_filter
+    q_lens = [int(wl.q_lens[i]) for i in idx]
+    kv_lens = [int(wl.kv_lens[i]) for i in idx]
+    n = len(idx)
+    G = 2 * MiB
+    max_ctx = max(kv_lens)
+    per_req = (max_ctx * shape.token_bytes + G - 1) // G * G
+    sess = KvSession(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, n, max_ctx, per_req * 2 * n, 1, G)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(wl.seed)
+    ids, _ = _fill_contexts(sess, torch, gen, shape, kv_lens, 1)
+    cu = [0]
+    for ql in q_lens:
+        cu.append(cu[-1] + ql)
+    q = torch.empty((cu[-1], shape.num_q_heads, shape.head_dim), device="cuda", dtype=torch.bfloat16)
+    for a in range(0, cu[-1], 16384):
+        b = min(cu[-1], a + 16384)
+        q[a:b] = torch.randn((b - a, shape.num_q_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    o = torch.empty_like(q)
+    scale = W.softmax_scale(shape.head_dim)
+    for _ in range(warmup):
+        sess.prefill(0, q, ids, cu, kv_lens, scale, out=o)
+    torch.cuda.synchronize()
+    sess.va.set_timing(True); sess.va.kernel_time(1)
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        sess.prefill(0, q, ids, cu, kv_lens, scale, out=o)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    k_ms, k_n = sess.va.kernel_time(1)
+    sess.va.set_timing(False)
+    flops = _prefill_flops(shape, q_lens, kv_lens)
+    ms = (t1 - t0) * 1e3 / iters
+    kms = k_ms / max(k_n, 1)
+    sess.close()
+    return {"ms_per_call": ms, "kernel_ms": kms, "tflops_call": flops / (ms * 1e9), "tflops_kernel": flops / (kms * 1e9),
+            "frac_of_mfma_peak": flops / (kms * 1e9) / MFMA_BF16_PEAK_TFLOPS, "flops": flops, "q_tokens": cu[-1]}
+
+
+def _measured_traffic(name):
+    p = os.path.join(ROOT, "profiles", "measured_traffic.json")
+    try:
+        with open(p) as f:
+            return json.load(f).get(name)
+    except Exception:
+        return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--only", choices=["all", "decode", "prefill"], default="all")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards by request / KV head with no exchange "
+              "step; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        return 2
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: the HIP path has no CPU fallback", file=sys.stderr)
+        return 1
+    import workloads as W
+
+    # A stream of its own: on the legacy default stream HIP serialises host-side copies with the device.
+    torch.cuda.set_stream(torch.cuda.Stream())
+
+    out = {"metric": "decode attn HBM GB/s (% of peak) + prefill attn TFLOP/s (% MFMA peak)", "unit": "GB/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "C2 Yi-6B-shaped decode: 64 requests, Hq=32 H=4 D=128, ctx U[1024,16384], "
+                                  "one token per request per step (step + append_kv + split-K decode + reduce), 2 MiB page-groups"}}
+    also = {}
+    if args.only in ("all", "decode"):
+        wl = W.config(1)
+        r = run_decode(args, torch, W, wl, args.steps, args.warmup, with_oracle=not args.no_cpu_baseline)
+        out["value"] = r["gbs_step"]
+        out["ms_per_step"] = r["ms_per_step"]
+        out["pct_of_hbm_peak"] = 100.0 * r["gbs_step"] / HBM_PEAK_GBS
+        out["roofline"] = {"kernel": "decode_splitk_kernel<128>", "bound": "hbm", "achieved": r["gbs_kernel"],
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": r["gbs_kernel"] / HBM_PEAK_GBS,
+                           "avg_launch_ms": r["kernel_ms"], "algorithmic_bytes_per_launch": r["bytes_per_step"],
+                           "traffic": _measured_traffic("decode_splitk_C2")}
+        if "cpu_baseline" in r:
+            out["cpu_baseline"] = r.pop("cpu_baseline")
+        out["decode_detail"] = {k: r[k] for k in ("reduce_ms", "tokens_in_batch", "map_calls_in_timed_region",
+                                                  "map_us_in_timed_region", "unmap_calls_in_timed_region")}
+    if args.only in ("all", "prefill"):
+        wl3 = W.config(2)
+        p = run_prefill(args, torch, W, wl3, iters=3, warmup=1)
+        also["C3_llama3_8b_prefill"] = {"tflops": p["tflops_call"], "kernel_tflops": p["tflops_kernel"],
+                                        "frac_of_bf16_mfma_peak": p["frac_of_mfma_peak"], "ms": p["ms_per_call"],
+                                        "kernel_ms": p["kernel_ms"], "q_tokens": p["q_tokens"],
+                                        "flop_convention": "causal only: 4*Hq*D per visible (query,key) pair",
+                                        "traffic": _measured_traffic("prefill_C3")}
+    if args.only == "all":
+        wl4 = W.config(3)
+        d4 = run_decode(args, torch, W, wl4, max(10, args.steps // 5), 3, layers=1, with_oracle=False, churn=True)
+        also["C4_yi34b_mixed_decode_part"] = {"gbs_step": d4["gbs_step"], "gbs_kernel": d4["gbs_kernel"],
+                                              "frac_of_hbm_peak_kernel": d4["gbs_kernel"] / HBM_PEAK_GBS,
+                                              "ms_per_step": d4["ms_per_step"], "kernel_ms": d4["kernel_ms"],
+                                              "map_calls": d4["map_calls_in_timed_region"], "map_us": d4["map_us_in_timed_region"],
+                                              "unmap_calls": d4["unmap_calls_in_timed_region"]}
+        p4 = run_prefill(args, torch, W, wl4, iters=5, warmup=1)
+        also["C4_yi34b_prefill_chunk"] = {"kernel_tflops": p4["tflops_kernel"], "frac_of_bf16_mfma_peak": p4["frac_of_mfma_peak"],
+                                          "kernel_ms": p4["kernel_ms"]}
+        wl5 = W.config(4)
+        p5 = run_prefill(args, torch, W, wl5, iters=2, warmup=1)
+        also["C5_long_prefill_131072"] = {"kernel_tflops": p5["tflops_kernel"], "frac_of_bf16_mfma_peak": p5["frac_of_mfma_peak"],
+                                          "kernel_ms": p5["kernel_ms"]}
+        wl5d = W.Workload("C5-decode", wl5.shape, wl5.seed, [1], [131072])
+        d5 = run_decode(args, torch, W, wl5d, 64, 5, layers=2, with_oracle=False)
+        also["C5_long_decode_131072"] = {"gbs_kernel": d5["gbs_kernel"], "frac_of_hbm_peak_kernel": d5["gbs_kernel"] / HBM_PEAK_GBS,
+                                         "kernel_ms": d5["kernel_ms"], "ms_per_step": d5["ms_per_step"]}
+    if args.only == "prefill":
+        p = also["C3_llama3_8b_prefill"]
+        out["value"] = p["kernel_tflops"]; out["unit"] = "TFLOP/s"; out["ms_per_step"] = p["ms"]
+        out["config"] = {"workload": "C3 Llama-3-8B-shaped causal prefill: 8 prompts U[4096,32768], Hq=32 H=8 D=128"}
+        out["roofline"] = {"kernel": "prefill_kernel<128>", "bound": "mfma", "achieved": p["kernel_tflops"],
+                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": p["frac_of_bf16_mfma_peak"],
+                           "traffic": p["traffic"]}
+    out["also"] = also
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

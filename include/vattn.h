@@ -132,8 +132,8 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q /*
 int64_t vattn_decode_workspace_bytes(vattn_ctx* ctx, const int64_t* kv_lens /*host*/, int n);
 
 /* Decode attention, one query token per request: q, o [n, Hq, D] bf16 (device).  Runs a split-K
- * kernel over fixed-size token chunks of every request's context followed by a reduce kernel that
- * merges the chunk partials (running maximum and sum) and writes bf16.  workspace: device memory
+ * kernel over equal segments of the batch's KV tiles followed by a reduce kernel that merges the
+ * partials of each request (running maximum and sum) and writes bf16.  workspace: device memory
  * of at least vattn_decode_workspace_bytes(), 256-byte aligned, private to this call until the
  * stream has passed it. */
 int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q /*device*/,
@@ -149,8 +149,13 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q /*d
 int vattn_set_timing(vattn_ctx* ctx, int enabled);
 int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* launches);
 
-/* Tuning knob: tokens per split-K chunk (multiple of 32; 0 = choose from the batch). */
+/* Tuning knobs of the split-K decode.  By default the library cuts the batch's 32-token tiles into as
+ * many equal segments as one launch keeps resident on the chip.  set_decode_chunk fixes the segment
+ * length instead (tokens, a multiple of 32; 0 = default).  set_decode_tuning chooses how many segments
+ * are cut per resident workgroup slot (>= 1; 1 measured best).  Results are identical up to
+ * floating-point summation order. */
 int vattn_set_decode_chunk(vattn_ctx* ctx, int tokens);
+int vattn_set_decode_tuning(vattn_ctx* ctx, int segments_per_slot);
 
 const char* vattn_last_error(void);
 

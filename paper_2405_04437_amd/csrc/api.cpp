@@ -34,14 +34,29 @@ bool check_request(vattn_ctx* ctx, int reqid, int64_t kv_len, const char* fn) {
     return true;
 }
 
-int choose_chunk(const vattn_ctx* ctx, const int64_t* kv_lens, int n) {
-    if (ctx->decode_chunk > 0) return ctx->decode_chunk;
-    int64_t total = 0;
-    for (int i = 0; i < n; ++i) total += kv_lens[i];
-    // Aim for a few thousand chunk workgroups so that all 256 CUs hold several; never below 64 tokens.
-    int chunk = 512;
-    while (chunk > 64 && total / chunk < 2048) chunk >>= 1;
-    return chunk;
+// Split-K plan: 32-token tiles of all requests form one sequence, cut into equal segments - as many
+// as one launch keeps resident on the chip (or a fixed tile count when the caller set a chunk size).
+struct DecodePlan { int64_t total_tiles; int tiles_per_seg; int num_segs; };
+DecodePlan plan_decode(const vattn_ctx* ctx, const int64_t* kv_lens, int n) {
+    DecodePlan p{0, 1, 1};
+    for (int i = 0; i < n; ++i) p.total_tiles += (kv_lens[i] + 31) / 32;
+    if (ctx->decode_chunk > 0) {
+        p.tiles_per_seg = ctx->decode_chunk / 32;
+    } else {
+        const int resident = decode_resident_workgroups(ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, ctx->cfg.head_dim, ctx->num_cus);
+        const int64_t segs = static_cast<int64_t>(resident) * ctx->decode_oversub;
+        p.tiles_per_seg = static_cast<int>((p.total_tiles + segs - 1) / segs);
+    }
+    if (p.tiles_per_seg < 1) p.tiles_per_seg = 1;
+    p.num_segs = static_cast<int>((p.total_tiles + p.tiles_per_seg - 1) / p.tiles_per_seg);
+    return p;
+}
+
+size_t decode_part_o_bytes(const vattn_ctx* ctx, const DecodePlan& p, int n) {
+    return align_up(static_cast<size_t>(p.num_segs + n) * ctx->cfg.num_q_heads * ctx->cfg.head_dim * 4, 256);
+}
+size_t decode_workspace_need(const vattn_ctx* ctx, const DecodePlan& p, int n) {
+    return decode_part_o_bytes(ctx, p, n) + align_up(static_cast<size_t>(p.num_segs + n) * ctx->cfg.num_q_heads * 2 * 4, 256);
 }
 
 }  // namespace
@@ -56,6 +71,7 @@ int vattn_init(const vattn_config* cfg, vattn_ctx** out) {
     if (!ctx) { set_error("init: out of host memory"); return -1; }
     ctx->cfg = *cfg;
     if (!ctx->mem.init(*cfg)) { delete ctx; return -1; }
+    if (!hip_ok(hipDeviceGetAttribute(&ctx->num_cus, hipDeviceAttributeMultiprocessorCount, cfg->device), "hipDeviceGetAttribute") || ctx->num_cus <= 0) { delete ctx; return -1; }
     *out = ctx;
     return 0;
 }
@@ -114,38 +130,38 @@ int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new, 
         if (ql < 0) { set_error("append_kv: cu_q must be non-decreasing"); return -1; }
         if (kv_len_before[r] < 0 || !check_request(ctx, reqids[r], kv_len_before[r] + ql, "append_kv")) return -1;
     }
-    const size_t off_cu = align_up(sizeof(int32_t) * n, 8);
-    const size_t off_kv = align_up(off_cu + sizeof(int32_t) * (n + 1), 8);
-    const size_t bytes = off_kv + sizeof(int64_t) * n;
-    char *h, *d;
-    if (!ctx->ring.acquire(bytes, &h, &d)) return -1;
-    std::memcpy(h, reqids, sizeof(int32_t) * n);
-    std::memcpy(h + off_cu, cu_q, sizeof(int32_t) * (n + 1));
-    std::memcpy(h + off_kv, kv_len_before, sizeof(int64_t) * n);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (!ctx->ring.commit(bytes, s)) return -1;
     AppendArgs a{};
     a.k_new = k_new; a.v_new = v_new;
     a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1);
     a.S = ctx->mem.S(); a.row_bytes = ctx->mem.T();
-    a.reqids = reinterpret_cast<const int32_t*>(d);
-    a.cu_q = reinterpret_cast<const int32_t*>(d + off_cu);
-    a.kv_before = reinterpret_cast<const int64_t*>(d + off_kv);
     a.n = n; a.total_rows = cu_q[n];
-    return launch_append_kv(a, s) ? 0 : -1;
+    if (n <= kInlineMaxReq) {
+        InlineMeta im;
+        for (int r = 0; r < n; ++r) { im.v[r] = reqids[r]; im.v[n + r] = static_cast<int32_t>(kv_len_before[r]); }
+        for (int r = 0; r <= n; ++r) im.v[2 * n + r] = cu_q[r];
+        a.inline_meta = 1;
+        return launch_append_kv(a, &im, s) ? 0 : -1;
+    }
+    const size_t off_kv = sizeof(int32_t) * n, off_cu = 2 * off_kv;
+    const size_t bytes = off_cu + sizeof(int32_t) * (n + 1);
+    char *h, *d;
+    if (!ctx->ring.acquire(bytes, &h, &d)) return -1;
+    std::memcpy(h, reqids, sizeof(int32_t) * n);
+    for (int r = 0; r < n; ++r) reinterpret_cast<int32_t*>(h + off_kv)[r] = static_cast<int32_t>(kv_len_before[r]);
+    std::memcpy(h + off_cu, cu_q, sizeof(int32_t) * (n + 1));
+    if (!ctx->ring.commit(bytes, s)) return -1;
+    a.reqids = reinterpret_cast<const int32_t*>(d);
+    a.kv_before = reinterpret_cast<const int32_t*>(d + off_kv);
+    a.cu_q = reinterpret_cast<const int32_t*>(d + off_cu);
+    return launch_append_kv(a, nullptr, s) ? 0 : -1;
 }
 
 int64_t vattn_decode_workspace_bytes(vattn_ctx* ctx, const int64_t* kv_lens, int n) {
     if (!ctx || n < 0 || (n > 0 && !kv_lens)) { set_error("decode_workspace_bytes: invalid argument"); return -1; }
-    // Sized for the smallest chunk the library may pick so that the answer does not depend on tuning.
-    int64_t chunks = 0;
-    const int min_chunk = ctx->decode_chunk > 0 ? ctx->decode_chunk : 64;
-    for (int i = 0; i < n; ++i) {
+    for (int i = 0; i < n; ++i)
         if (kv_lens[i] < 1) { set_error("decode_workspace_bytes: context lengths must be >= 1"); return -1; }
-        chunks += (kv_lens[i] + min_chunk - 1) / min_chunk;
-    }
-    const int64_t per_chunk = static_cast<int64_t>(ctx->cfg.num_q_heads) * (ctx->cfg.head_dim + 2) * 4;
-    return align_up(static_cast<size_t>(chunks * per_chunk), 256) + 256;
+    return static_cast<int64_t>(decode_workspace_need(ctx, plan_decode(ctx, kv_lens, n), n));
 }
 
 int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
@@ -157,45 +173,50 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, vo
         if (kv_lens[r] < 1) { set_error("attn_decode: context length must be >= 1"); return -1; }
         if (!check_request(ctx, reqids[r], kv_lens[r], "attn_decode")) return -1;
     }
-    const int chunk = choose_chunk(ctx, kv_lens, n);
+    const DecodePlan plan = plan_decode(ctx, kv_lens, n);
+    if (plan.total_tiles > INT32_MAX) { set_error("attn_decode: batch too large"); return -1; }
+    const bool inl = n <= kInlineMaxReq;
+    InlineMeta im;
     const size_t off_kv = sizeof(int32_t) * n, off_cu = off_kv * 2;
     const size_t bytes = off_cu + sizeof(int32_t) * (n + 1);
-    char *h, *d;
-    if (!ctx->ring.acquire(bytes, &h, &d)) return -1;
-    int32_t* h_req = reinterpret_cast<int32_t*>(h);
-    int32_t* h_kv = reinterpret_cast<int32_t*>(h + off_kv);
-    int32_t* h_cu = reinterpret_cast<int32_t*>(h + off_cu);
+    char *h = nullptr, *d = nullptr;
+    if (!inl && !ctx->ring.acquire(bytes, &h, &d)) return -1;
+    int32_t* h_req = inl ? im.v : reinterpret_cast<int32_t*>(h);
+    int32_t* h_kv = inl ? im.v + n : reinterpret_cast<int32_t*>(h + off_kv);
+    int32_t* h_cu = inl ? im.v + 2 * n : reinterpret_cast<int32_t*>(h + off_cu);
     int64_t total = 0;
     for (int r = 0; r < n; ++r) {
         h_req[r] = reqids[r];
         h_kv[r] = static_cast<int32_t>(kv_lens[r]);
         h_cu[r] = static_cast<int32_t>(total);
-        total += (kv_lens[r] + chunk - 1) / chunk;
+        total += (kv_lens[r] + 31) / 32;
     }
     h_cu[n] = static_cast<int32_t>(total);
     const int Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
-    const size_t part_o_bytes = align_up(static_cast<size_t>(total) * Hq * D * 4, 256);
-    const size_t need = part_o_bytes + static_cast<size_t>(total) * Hq * 2 * 4;
+    const size_t part_o_bytes = decode_part_o_bytes(ctx, plan, n);
+    const size_t need = decode_workspace_need(ctx, plan, n);
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) { set_error("attn_decode: workspace must be 256-byte aligned"); return -1; }
     if (workspace_bytes < need) { set_error("attn_decode: workspace too small (" + std::to_string(workspace_bytes) + " < " + std::to_string(need) + ")"); return -1; }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (!ctx->ring.commit(bytes, s)) return -1;
+    if (!inl && !ctx->ring.commit(bytes, s)) return -1;
 
     DecodeArgs a{};
     a.q = q; a.o = o;
     a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1); a.S = ctx->mem.S();
     a.Hq = Hq; a.H = ctx->cfg.num_kv_heads; a.D = D;
+    a.inline_meta = inl ? 1 : 0;
     a.reqids = reinterpret_cast<const int32_t*>(d);
     a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
-    a.cu_chunks = reinterpret_cast<const int32_t*>(d + off_cu);
-    a.n = n; a.total_chunks = static_cast<int>(total); a.chunk_tokens = chunk; a.scale = scale;
+    a.cu_tiles = reinterpret_cast<const int32_t*>(d + off_cu);
+    a.n = n; a.total_tiles = static_cast<int>(total); a.tiles_per_seg = plan.tiles_per_seg; a.num_segs = plan.num_segs; a.scale = scale;
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + part_o_bytes);
+    const InlineMeta* imp = inl ? &im : nullptr;
     if (ctx->timing && !ctx->timers[0].begin(s)) return -1;
-    if (!launch_decode_splitk(a, s)) return -1;
+    if (!launch_decode_splitk(a, imp, s)) return -1;
     if (ctx->timing && !ctx->timers[0].end(s)) return -1;
     if (ctx->timing && !ctx->timers[2].begin(s)) return -1;
-    if (!launch_decode_reduce(a, s)) return -1;
+    if (!launch_decode_reduce(a, imp, s)) return -1;
     if (ctx->timing && !ctx->timers[2].end(s)) return -1;
     return 0;
 }
@@ -284,6 +305,15 @@ int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* laun
 int vattn_set_decode_chunk(vattn_ctx* ctx, int tokens) {
     if (!ctx || tokens < 0 || tokens % 32 != 0) { set_error("set_decode_chunk: tokens must be a non-negative multiple of 32"); return -1; }
     ctx->decode_chunk = tokens;
+    return 0;
+}
+
+int vattn_set_decode_tuning(vattn_ctx* ctx, int segments_per_slot) {
+    if (!ctx || segments_per_slot < 1 || segments_per_slot > 64) {
+        set_error("set_decode_tuning: segments_per_slot must be in [1,64]");
+        return -1;
+    }
+    ctx->decode_oversub = segments_per_slot;
     return 0;
 }
 

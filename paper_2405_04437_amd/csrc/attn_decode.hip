@@ -2,16 +2,20 @@
 //
 // What is computed is Eq. 2 of the paper for one query token per request, o = softmax(q K^T * scale) V,
 // with K, V read straight from the request's sub-tensor at base + reqId*S (Sec. 5.2.3) - the kernel
-// never consults a block table.  The context is cut into fixed-size token chunks; every (chunk,
-// KV head) pair is handled by ONE wavefront that keeps a running maximum m, a running sum l and an
-// un-normalised output for the query heads of its KV head (the split-K scheme the paper cites as
-// FlashDecoding); a second kernel merges the chunk partials.
+// never consults a block table.  The contexts of all requests, cut into 32-token tiles, form one
+// global tile sequence that is split into equal segments, one per resident workgroup, so that every
+// workgroup moves the same number of bytes and the launch is a single balanced round.  Every
+// (segment, KV head) pair is handled by ONE wavefront that keeps a running maximum m, a running sum l
+// and an un-normalised output for the query heads of its KV head (the split-K scheme the paper cites
+// as FlashDecoding); a segment that crosses a request boundary emits one partial per request.  A
+// second kernel merges the partials of each request.
 //
 // gfx950 mapping
 //  * The path is HBM-bound (8 or 7 flops per KV byte), so the design goal is a deep, fully coalesced
 //    load stream: the waves of a workgroup take the KV heads of the SAME token range, so together
-//    they read one contiguous byte range of K and one of V.  Every lane loads 16 bytes; a wave has
-//    16 such loads in flight (one 32-token tile of K and of V) while it computes the previous tile.
+//    they read one contiguous byte range of K and one of V.  Every lane loads 16 bytes through a raw
+//    buffer resource (scalar base + scalar tile offset + one per-lane offset); a wave has 16 such loads
+//    in flight (one 32-token tile of K and of V) while it computes the previous tile.
 //  * The two contractions run on the matrix cores (v_mfma_f32_16x16x32_bf16).  Scores are computed
 //    transposed, S^T = K Q^T (tokens x heads), so that each lane owns one query head: the softmax
 //    state is per lane, and the exponentiated scores are already in the register layout the second
@@ -36,6 +40,9 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 constexpr int kTile = 32;          // tokens per inner iteration of a wave
 constexpr int kMaxWaves = 8;       // waves (KV heads) per workgroup
 constexpr float kLog2e = 1.4426950408889634f;
+// Fourth dword of a gfx9-family raw buffer resource: 32-bit data format, no swizzle, no stride.
+constexpr int kRsrcWord3 = 0x00020000;
+constexpr int kAuxNt = 2;  // cache-policy bit "nt": streamed once, do not keep in the caches
 
 template <int D> struct Geo {
     static constexpr int RB = D * 2;              // bytes of one head row
@@ -49,11 +56,17 @@ template <int D> struct Geo {
 
 __device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask)); }
 
-template <int D>
-__global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArgs a, int units, int hb_per_kv) {
+// INL: the index arrays are read from the kernel-argument segment (InlineMeta) instead of global memory;
+// a compile-time switch so that both variants keep these uniform reads on the scalar unit.
+template <int D, bool INL>
+__global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArgs a, int units, int hb_per_kv, InlineMeta im) {
     using G = Geo<D>;
+    auto reqid_of = [&](int r) { if constexpr (INL) return im.v[r]; else return a.reqids[r]; };
+    auto kvlen_of = [&](int r) { if constexpr (INL) return im.v[a.n + r]; else return a.kv_lens[r]; };
+    auto cu_of = [&](int r) { if constexpr (INL) return im.v[2 * a.n + r]; else return a.cu_tiles[r]; };
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    const int wave = threadIdx.x >> 6;
+    // the wave index is uniform within a wave: saying so keeps the KV-head arithmetic on the scalar unit
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l = threadIdx.x & 63;
     const int unit = blockIdx.y * (blockDim.x >> 6) + wave;
     if (unit >= units) return;  // no workgroup barrier is ever used, so leaving early is safe
@@ -61,30 +74,37 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
     const int hb = unit - kvh * hb_per_kv;
     const int group = a.Hq / a.H;
 
-    // which request does this chunk belong to: largest r with cu_chunks[r] <= chunk
-    const int chunk = blockIdx.x;
+    // this segment's slice of the global tile sequence, and the request its first tile belongs to
+    const int seg = blockIdx.x;
+    const int T0 = seg * a.tiles_per_seg;
+    const int T1 = min(T0 + a.tiles_per_seg, a.total_tiles);
     int lo = 0, hi = a.n;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (a.cu_chunks[mid] <= chunk) lo = mid; else hi = mid;
+        if (cu_of(mid) <= T0) lo = mid; else hi = mid;
     }
-    const int req = lo;
-    const int kv_len = a.kv_lens[req];
-    const int tok0 = (chunk - a.cu_chunks[req]) * a.chunk_tokens;
-    const int tok1 = min(tok0 + a.chunk_tokens, kv_len);
     const int64_t row_stride = static_cast<int64_t>(a.H) * G::RB;
-    const int64_t sub = static_cast<int64_t>(a.reqids[req]) * a.S + static_cast<int64_t>(kvh) * G::RB;
-    const char* kp = a.k_base + sub;
-    const char* vp = a.v_base + sub;
-
     char* klds = lds_raw + wave * G::WAVE_LDS;
     char* vlds = klds + kTile * G::KSTR;
-
-    // Query heads of this wave as B operands of S^T = K Q^T: lane (n = l%16, j = l/16) holds
-    // Q[head n][kb*32 + j*8 .. +8].
     const int hl = hb * 16 + (l & 15);
     const bool head_ok = hl < group;
     const int head = kvh * group + hl;
+    const float scale_log2 = a.scale * kLog2e;
+
+  int g0 = T0;
+  for (int req = lo; g0 < T1; ++req) {
+    // piece = tiles [g0, g1) of request req
+    const int r_first = cu_of(req);
+    const int g1 = min(T1, cu_of(req + 1));
+    const int kv_len = kvlen_of(req);
+    const int tok0 = (g0 - r_first) * kTile;
+    const int tok1 = min((g1 - r_first) * kTile, kv_len);
+    const int64_t sub = static_cast<int64_t>(reqid_of(req)) * a.S + static_cast<int64_t>(kvh) * G::RB;
+    const char* kp = a.k_base + sub;
+    const char* vp = a.v_base + sub;
+
+    // Query heads of this wave as B operands of S^T = K Q^T: lane (n = l%16, j = l/16) holds
+    // Q[head n][kb*32 + j*8 .. +8].
     bf16x8 qb[D / 32];
     {
         const char* qrow = static_cast<const char*>(a.q) + (static_cast<int64_t>(req) * a.Hq + (head_ok ? head : 0)) * G::RB;
@@ -99,27 +119,28 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
     const int ld_row = l / G::LPR;            // row inside one load instruction
     const int ld_col = (l % G::LPR) * 16;     // byte offset inside the row
     u32x4 kreg[G::NL], vreg[G::NL];
-    auto issue_loads = [&](int t) {
+    // K and V of this (request, KV head) as raw buffer resources: the loads then take one 32-bit
+    // per-lane offset plus a scalar offset, so all tile/row address arithmetic runs on the scalar unit.
+    // num_records ends at the last valid row of this head: the hardware range check is a second guard
+    // behind the explicit clamp below (out-of-range buffer reads return zero instead of faulting).
+    const int nrec = (kv_len - 1) * static_cast<int>(row_stride) + G::RB;
+    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kp), 0, nrec, kRsrcWord3);
+    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vp), 0, nrec, kRsrcWord3);
+    auto issue_loads = [&](u32x4 (&kreg)[G::NL], u32x4 (&vreg)[G::NL], int t) {
+        // Rows past the end of the context (ragged last tile) are clamped to the last valid token, so
+        // nothing beyond what step() has mapped is ever read; their scores are masked below.  The clamp
+        // is branch-free (a few VALU ops per tile) so that the load/wait order stays static.
+        const int first = tok0 + t * kTile;
+        const int sbase = first * static_cast<int>(row_stride);
+        const int last = kv_len - 1 - first;
 #pragma unroll
         for (int i = 0; i < G::NL; ++i) {
-            // rows past the end of the context are clamped to the last valid token: never read
-            // beyond what step() has mapped; their scores are masked below.
-            const int tok = min(tok0 + t * kTile + i * G::RPI + ld_row, kv_len - 1);
-            const int64_t off = static_cast<int64_t>(tok) * row_stride + ld_col;
-            kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + off));
-            vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vp + off));
+            const int off = min(i * G::RPI + ld_row, last) * static_cast<int>(row_stride) + ld_col;
+            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, off, sbase, kAuxNt);
+            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, off, sbase, kAuxNt);
         }
     };
-
-    const float scale_log2 = a.scale * kLog2e;
-    float m = -INFINITY, lsum = 0.f;
-    f32x4 o[D / 16];
-#pragma unroll
-    for (int db = 0; db < D / 16; ++db) o[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    const int ntiles = (tok1 - tok0 + kTile - 1) / kTile;
-    issue_loads(0);
-    for (int t = 0; t < ntiles; ++t) {
+    auto stage = [&](const u32x4 (&kreg)[G::NL], const u32x4 (&vreg)[G::NL]) {
 #pragma unroll
         for (int i = 0; i < G::NL; ++i) {
             const int row = i * G::RPI + ld_row;
@@ -128,8 +149,14 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        if (t + 1 < ntiles) issue_loads(t + 1);
+    };
 
+    float m = -INFINITY, lsum = 0.f;
+    f32x4 o[D / 16];
+#pragma unroll
+    for (int db = 0; db < D / 16; ++db) o[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto compute = [&](int t) {
         // S^T tiles: 2 x (16 tokens x 16 heads)
         f32x4 s[2];
 #pragma unroll
@@ -185,76 +212,154 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();
+    };
+
+    const int ntiles = g1 - g0;
+    // One tile of K and V (16 loads of 16 B per lane) is in flight while the previous one is multiplied.
+    // (A second register set, two tiles in flight, was measured and bought nothing: with 8 waves per CU
+    // the memory system is already saturated.)
+    issue_loads(kreg, vreg, 0);
+    for (int t = 0; t < ntiles; ++t) {
+        stage(kreg, vreg);
+        if (t + 1 < ntiles) issue_loads(kreg, vreg, t + 1);
+        compute(t);
     }
 
     lsum += __shfl_xor(lsum, 16);
     lsum += __shfl_xor(lsum, 32);
     if (head_ok) {
-        float* po = a.part_o + (static_cast<int64_t>(chunk) * a.Hq + head) * D + (l >> 4) * 4;
+        const int64_t slot = static_cast<int64_t>(seg) + req;
+        float* po = a.part_o + (slot * a.Hq + head) * D + (l >> 4) * 4;
 #pragma unroll
         for (int db = 0; db < D / 16; ++db) *reinterpret_cast<f32x4*>(po + db * 16) = o[db];
         if ((l >> 4) == 0) {
-            float* pml = a.part_ml + (static_cast<int64_t>(chunk) * a.Hq + head) * 2;
+            float* pml = a.part_ml + (slot * a.Hq + head) * 2;
             pml[0] = m;
             pml[1] = lsum;
         }
     }
+    g0 = g1;
+  }
 }
 
-// Merge of the chunk partials: with M = max_s m_s,  o = sum_s 2^(m_s-M) o_s / sum_s 2^(m_s-M) l_s.
-// One workgroup per (request, query head), one thread per output channel.
-template <int D>
-__global__ __launch_bounds__(D) void decode_reduce_kernel(DecodeArgs a) {
+// Merge of the segment partials of one (request, query head):
+//   M = max_s m_s,   o = sum_s 2^(m_s-M) o_s / sum_s 2^(m_s-M) l_s.
+// One workgroup of kReduceWaves waves per (request, head).  Pass 1: all threads scan the m_s for the
+// maximum.  Pass 2: wave w takes chunks w, w+W, ... (lanes cover the channels, 2 per lane for
+// D = 128) with independent multiply-adds, so the loads of many chunks are in flight at once; the
+// wave sums are combined through LDS.
+constexpr int kReduceWaves = 8;
+
+template <int D, bool INL>
+__global__ __launch_bounds__(kReduceWaves * 64) void decode_reduce_kernel(DecodeArgs a, InlineMeta im) {
+    constexpr int V = D / 64;  // channels per lane
     const int req = blockIdx.x / a.Hq;
     const int head = blockIdx.x - req * a.Hq;
-    const int c0 = a.cu_chunks[req], c1 = a.cu_chunks[req + 1];
-    const int d = threadIdx.x;
+    // partial slots of this request: segments floor(first tile / tps) .. floor(last tile / tps), + req
+    int t_first, t_end;
+    if constexpr (INL) { t_first = im.v[2 * a.n + req]; t_end = im.v[2 * a.n + req + 1]; }
+    else { t_first = a.cu_tiles[req]; t_end = a.cu_tiles[req + 1]; }
+    const int c0 = t_first / a.tiles_per_seg + req;
+    const int c1 = (t_end - 1) / a.tiles_per_seg + req + 1;
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    __shared__ float sh_max[kReduceWaves];
+    __shared__ float sh_acc[kReduceWaves][D];
+    __shared__ float sh_den[kReduceWaves];
+
     float M = -INFINITY;
-    for (int c = c0; c < c1; ++c) M = fmaxf(M, a.part_ml[(static_cast<int64_t>(c) * a.Hq + head) * 2]);
-    float num = 0.f, den = 0.f;
-    for (int c = c0; c < c1; ++c) {
+    for (int c = c0 + static_cast<int>(threadIdx.x); c < c1; c += kReduceWaves * 64)
+        M = fmaxf(M, a.part_ml[(static_cast<int64_t>(c) * a.Hq + head) * 2]);
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) M = fmaxf(M, __shfl_xor(M, sft));
+    if (l == 0) sh_max[w] = M;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kReduceWaves; ++i) M = fmaxf(M, sh_max[i]);   // finite: c1 > c0 always
+
+    float den = 0.f, acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+#pragma unroll 4
+    for (int c = c0 + w; c < c1; c += kReduceWaves) {
         const int64_t idx = static_cast<int64_t>(c) * a.Hq + head;
-        const float w = __builtin_amdgcn_exp2f(a.part_ml[idx * 2] - M);
-        den += w * a.part_ml[idx * 2 + 1];
-        num += w * a.part_o[idx * D + d];
+        const float f = __builtin_amdgcn_exp2f(a.part_ml[idx * 2] - M);
+        den += f * a.part_ml[idx * 2 + 1];
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[e] += f * a.part_o[idx * D + l * V + e];
     }
-    __bf16* out = static_cast<__bf16*>(a.o) + (static_cast<int64_t>(req) * a.Hq + head) * D + d;
-    *out = static_cast<__bf16>(num / den);
+#pragma unroll
+    for (int e = 0; e < V; ++e) sh_acc[w][l * V + e] = acc[e];
+    if (l == 0) sh_den[w] = den;
+    __syncthreads();
+    if (w == 0) {
+        float dt = 0.f, out[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) out[e] = 0.f;
+#pragma unroll
+        for (int i = 0; i < kReduceWaves; ++i) {
+            dt += sh_den[i];
+#pragma unroll
+            for (int e = 0; e < V; ++e) out[e] += sh_acc[i][l * V + e];
+        }
+        __bf16* dst = static_cast<__bf16*>(a.o) + (static_cast<int64_t>(req) * a.Hq + head) * D + l * V;
+        const float inv = 1.f / dt;
+#pragma unroll
+        for (int e = 0; e < V; ++e) dst[e] = static_cast<__bf16>(out[e] * inv);
+    }
 }
 
 }  // namespace
 
-bool launch_decode_splitk(const DecodeArgs& a, hipStream_t stream) {
+static const InlineMeta kNoInline{};
+
+static int waves_per_workgroup(int Hq, int H) {
+    const int units = H * ((Hq / H + 15) / 16);
+    return units < kMaxWaves ? units : kMaxWaves;
+}
+
+// A CU holds kMaxWaves waves of this kernel (LDS bound: one wave-private K/V stage each).
+int decode_resident_workgroups(int Hq, int H, int D, int num_cus) {
+    (void)D;
+    const int units = H * ((Hq / H + 15) / 16);
+    const int waves = waves_per_workgroup(Hq, H);
+    const int wg_per_cu = kMaxWaves / waves;
+    const int ygrid = (units + waves - 1) / waves;
+    const int segs = num_cus * wg_per_cu / ygrid;
+    return segs > 0 ? segs : 1;
+}
+
+bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream) {
+    const InlineMeta& meta = im ? *im : kNoInline;
     const int group = a.Hq / a.H;
     const int hb_per_kv = (group + 15) / 16;
     const int units = a.H * hb_per_kv;
-    const int waves = units < kMaxWaves ? units : kMaxWaves;
-    dim3 grid(static_cast<unsigned>(a.total_chunks), static_cast<unsigned>((units + waves - 1) / waves));
+    const int waves = waves_per_workgroup(a.Hq, a.H);
+    dim3 grid(static_cast<unsigned>(a.num_segs), static_cast<unsigned>((units + waves - 1) / waves));
     dim3 block(static_cast<unsigned>(waves * 64));
-    if (a.D == 128) {
-        const size_t lds = static_cast<size_t>(waves) * Geo<128>::WAVE_LDS;
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(decode_splitk_kernel<128>), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxWaves * Geo<128>::WAVE_LDS), "hipFuncSetAttribute")) return false;
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(decode_splitk_kernel<128>, grid, block, lds, stream, a, units, hb_per_kv);
-    } else {
-        const size_t lds = static_cast<size_t>(waves) * Geo<64>::WAVE_LDS;
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(decode_splitk_kernel<64>), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxWaves * Geo<64>::WAVE_LDS), "hipFuncSetAttribute")) return false;
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(decode_splitk_kernel<64>, grid, block, lds, stream, a, units, hb_per_kv);
-    }
+    auto launch = [&](auto kernel, size_t wave_lds) -> bool {
+        // dynamic LDS above 64 KiB has to be allowed per kernel; the call is cheap and idempotent
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxWaves * wave_lds)), "hipFuncSetAttribute")) return false;
+        hipLaunchKernelGGL(kernel, grid, block, static_cast<size_t>(waves) * wave_lds, stream, a, units, hb_per_kv, meta);
+        return true;
+    };
+    bool ok;
+    if (a.D == 128) ok = a.inline_meta ? launch(decode_splitk_kernel<128, true>, Geo<128>::WAVE_LDS) : launch(decode_splitk_kernel<128, false>, Geo<128>::WAVE_LDS);
+    else ok = a.inline_meta ? launch(decode_splitk_kernel<64, true>, Geo<64>::WAVE_LDS) : launch(decode_splitk_kernel<64, false>, Geo<64>::WAVE_LDS);
+    if (!ok) return false;
     return hip_ok(hipGetLastError(), "decode split-K launch");
 }
 
-bool launch_decode_reduce(const DecodeArgs& a, hipStream_t stream) {
+bool launch_decode_reduce(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream) {
+    const InlineMeta& meta = im ? *im : kNoInline;
     dim3 grid(static_cast<unsigned>(a.n * a.Hq));
-    if (a.D == 128) hipLaunchKernelGGL(decode_reduce_kernel<128>, grid, dim3(128), 0, stream, a);
-    else hipLaunchKernelGGL(decode_reduce_kernel<64>, grid, dim3(64), 0, stream, a);
+    const dim3 block(kReduceWaves * 64);
+    if (a.D == 128) {
+        if (a.inline_meta) hipLaunchKernelGGL((decode_reduce_kernel<128, true>), grid, block, 0, stream, a, meta);
+        else hipLaunchKernelGGL((decode_reduce_kernel<128, false>), grid, block, 0, stream, a, meta);
+    } else {
+        if (a.inline_meta) hipLaunchKernelGGL((decode_reduce_kernel<64, true>), grid, block, 0, stream, a, meta);
+        else hipLaunchKernelGGL((decode_reduce_kernel<64, false>), grid, block, 0, stream, a, meta);
+    }
     return hip_ok(hipGetLastError(), "decode reduce launch");
 }
 

@@ -11,7 +11,11 @@ namespace {
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 // grid.x covers 16-byte pieces of the packed new rows; grid.y = 0 for K, 1 for V.
-__global__ __launch_bounds__(256) void append_kv_kernel(AppendArgs a) {
+template <bool INL>
+__global__ __launch_bounds__(256) void append_kv_kernel(AppendArgs a, InlineMeta im) {
+    auto reqid_of = [&](int r) { if constexpr (INL) return im.v[r]; else return a.reqids[r]; };
+    auto before_of = [&](int r) { if constexpr (INL) return im.v[a.n + r]; else return a.kv_before[r]; };
+    auto cu_of = [&](int r) { if constexpr (INL) return im.v[2 * a.n + r]; else return a.cu_q[r]; };
     const int64_t pieces_per_row = a.row_bytes / 16;
     const int64_t total = static_cast<int64_t>(a.total_rows) * pieces_per_row;
     const char* src = static_cast<const char*>(blockIdx.y == 0 ? a.k_new : a.v_new);
@@ -24,23 +28,25 @@ __global__ __launch_bounds__(256) void append_kv_kernel(AppendArgs a) {
         int lo = 0, hi = a.n;
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (a.cu_q[mid] <= row) lo = mid; else hi = mid;
+            if (cu_of(mid) <= row) lo = mid; else hi = mid;
         }
-        const int64_t tok = a.kv_before[lo] + (row - a.cu_q[lo]);
-        char* dst = dst_base + static_cast<int64_t>(a.reqids[lo]) * a.S + tok * a.row_bytes + piece * 16;
+        const int64_t tok = static_cast<int64_t>(before_of(lo)) + (row - cu_of(lo));
+        char* dst = dst_base + static_cast<int64_t>(reqid_of(lo)) * a.S + tok * a.row_bytes + piece * 16;
         *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(src + i * 16);
     }
 }
 
 }  // namespace
 
-bool launch_append_kv(const AppendArgs& a, hipStream_t stream) {
+bool launch_append_kv(const AppendArgs& a, const InlineMeta* im, hipStream_t stream) {
     if (a.total_rows == 0) return true;
     const int64_t total = static_cast<int64_t>(a.total_rows) * (a.row_bytes / 16);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 8192) blocks = 8192;
     dim3 grid(static_cast<unsigned>(blocks), 2);
-    hipLaunchKernelGGL(append_kv_kernel, grid, dim3(256), 0, stream, a);
+    static const InlineMeta kNoInline{};
+    if (a.inline_meta && im) hipLaunchKernelGGL(append_kv_kernel<true>, grid, dim3(256), 0, stream, a, *im);
+    else hipLaunchKernelGGL(append_kv_kernel<false>, grid, dim3(256), 0, stream, a, kNoInline);
     return hip_ok(hipGetLastError(), "append_kv launch");
 }
 

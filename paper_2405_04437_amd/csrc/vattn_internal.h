@@ -91,28 +91,40 @@ struct KernelTimer {
 // ---------------------------------------------------------------------------------------------
 // Kernel launchers (one per .hip file).  All pointers are device pointers.
 // ---------------------------------------------------------------------------------------------
+// Small index arrays travel inside the kernel-argument segment (no upload, no staging buffer) when
+// they fit; larger batches go through the pinned staging ring and are read through pointers.
+constexpr int kInlineMaxReq = 256;
+struct InlineMeta { int32_t v[3 * kInlineMaxReq + 2]; };
+
 struct AppendArgs {
     const void* k_new; const void* v_new;   // [rows, H, D] bf16
     char* k_base; char* v_base;             // buffer bases of the layer
     int64_t S;                              // bytes between consecutive reqIds
     int64_t row_bytes;                      // H*D*P
-    const int32_t* reqids; const int32_t* cu_q; const int64_t* kv_before;  // device, n / n+1 / n
+    const int32_t* reqids; const int32_t* cu_q; const int32_t* kv_before;  // device, n / n+1 / n
     int n; int total_rows;
+    int inline_meta;                        // 1: arrays are in InlineMeta as [reqids | kv_before | cu_q]
 };
-bool launch_append_kv(const AppendArgs& a, hipStream_t stream);
+bool launch_append_kv(const AppendArgs& a, const InlineMeta* im, hipStream_t stream);
 
 struct DecodeArgs {
     const void* q; void* o;                 // [n, Hq, D] bf16
     const char* k_base; const char* v_base; int64_t S;
     int Hq, H, D;
-    const int32_t* reqids; const int32_t* kv_lens; const int32_t* cu_chunks;  // device: n, n, n+1
-    int n; int total_chunks; int chunk_tokens;
+    // Split-K partition: the contexts of all requests, cut into 32-token tiles, form one global tile
+    // sequence (request-major).  Segment s owns tiles [s*tiles_per_seg, (s+1)*tiles_per_seg); a segment
+    // that crosses a request boundary produces one partial per request it touches.  The partial of
+    // (segment s, request r) lives in slot s + r (strictly increasing along the sequence, so unique).
+    const int32_t* reqids; const int32_t* kv_lens; const int32_t* cu_tiles;  // device: n, n, n+1
+    int n; int total_tiles; int tiles_per_seg; int num_segs;
     float scale;
-    float* part_o;   // [total_chunks, Hq, D] un-normalised partial outputs
-    float* part_ml;  // [total_chunks, Hq, 2] running max (log2 domain) and partial sum
+    float* part_o;   // [num_segs + n, Hq, D] un-normalised partial outputs
+    float* part_ml;  // [num_segs + n, Hq, 2] running max (log2 domain) and partial sum
+    int inline_meta; // 1: arrays are in InlineMeta as [reqids | kv_lens | cu_tiles]
 };
-bool launch_decode_splitk(const DecodeArgs& a, hipStream_t stream);
-bool launch_decode_reduce(const DecodeArgs& a, hipStream_t stream);
+int decode_resident_workgroups(int Hq, int H, int D, int num_cus);  // workgroups one launch keeps resident
+bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream);
+bool launch_decode_reduce(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream);
 
 struct PrefillItem { int32_t req; int32_t kvh; int32_t q_tile; int32_t pad; };
 struct PrefillArgs {
@@ -137,4 +149,6 @@ struct vattn_ctx {
     vattn::KernelTimer timers[3];
     bool timing = false;
     int decode_chunk = 0;
+    int decode_oversub = 1;  // segments per resident workgroup slot
+    int num_cus = 0;
 };
