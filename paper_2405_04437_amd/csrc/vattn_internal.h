@@ -135,6 +135,7 @@ struct PrefillArgs {
     const PrefillItem* items;               // device: 8 queues of items_per_xcd entries each
     int items_per_xcd; int n;
     float scale;
+    int dbg;
 };
 int prefill_tile_rows(int Hq, int H, int D);     // query positions covered by one work item
 int prefill_heads_per_item(int Hq, int H, int D);
