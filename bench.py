@@ -79,7 +79,7 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
     shape = wl.shape
     n = sum(1 for q in wl.q_lens if q == 1)
     kv_lens = [int(x) for x in wl.kv_lens[:n]]
-    total_steps = steps + warmup + 2
+    total_steps = 2 * steps + warmup + 2
     ctx_hi = wl.extra["ctx_range"][1] if churn else 0
     max_ctx = max(max(kv_lens), ctx_hi) + total_steps + 8
     G = 2 * MiB
@@ -90,59 +90,84 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
                      POLICY_DEFERRED)
     gen = torch.Generator(device="cuda"); gen.manual_seed(wl.seed)
     ids, host = _fill_contexts(sess, torch, gen, shape, kv_lens, layers, keep_host=with_oracle)
+    for r, L in zip(ids, kv_lens):
+        sess.seq_lens[r] = L
     scale = W.softmax_scale(shape.head_dim)
     q = torch.randn((n, shape.num_q_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     knew = torch.randn((n, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     vnew = torch.randn((n, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     o = torch.empty_like(q)
-    lens = list(kv_lens)
-    ws = sess.workspace([max(L, ctx_hi) + total_steps for L in lens])
+    import numpy as np
+    lens = np.array(kv_lens, dtype=np.int64)
+    ids = np.array(ids, dtype=np.int32)
+    seq = np.zeros(sess.B, dtype=np.int64)      # cache_seq_len of Algorithm 1, indexed by reqId
+    ws = sess.workspace([max(int(L), ctx_hi) + total_steps for L in lens])
     if churn:  # source rows for the K/V of newly arriving requests (their prefill's KV write)
         kbig = torch.randn((ctx_hi, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
         vbig = torch.randn((ctx_hi, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
-    cu = list(range(n + 1))
-    rng = __import__("numpy").random.default_rng(wl.seed)
+    cu = np.arange(n + 1, dtype=np.int32)
+    rng = np.random.default_rng(wl.seed)
+    per_tok = 2 * shape.num_kv_heads * shape.head_dim * 2
+    qo_bytes = n * 2 * shape.num_q_heads * shape.head_dim * 2
+    va, stream = sess.va, sess.stream
+    torch_stream = torch.cuda.current_stream()
 
     def one_step(i):
-        nonlocal lens, ids
         if churn:  # config 4: ~10% of the requests finish and as many arrive, reusing backed reqIds
             k = max(1, int(round(0.10 * n)))
             arrivals = []
             for slot in rng.choice(n, size=k, replace=False):
-                sess.finish(ids[slot])
+                seq[ids[slot]] = 0
+                assert va.free_reqid(int(ids[slot])) == 0
                 lens[slot] = int(rng.integers(wl.extra["ctx_range"][0], wl.extra["ctx_range"][1], endpoint=True))
-                ids[slot] = sess.admit(lens[slot])
+                ids[slot] = va.alloc_reqid()
+                seq[ids[slot]] = lens[slot]
                 arrivals.append(slot)
-            sess.step()
+            assert va.step(seq) == 0
             for slot in arrivals:  # the newcomer's context is written in place (contiguous copy)
+                L = int(lens[slot])
                 for layer in range(layers):
-                    sess.append(layer, kbig[:lens[slot]], vbig[:lens[slot]], [ids[slot]], [0, lens[slot]], [0])
-        before = list(lens)
-        for r, L in zip(ids, lens):
-            sess.seq_lens[r] = L + 1
-        sess.step()
+                    assert va.append_kv(layer, stream, kbig[:L], vbig[:L], ids[slot:slot + 1], [0, L], [0]) == 0
+        seq[ids] = lens + 1
+        assert va.step(seq) == 0
         for layer in range(layers):
-            sess.append(layer, knew, vnew, ids, cu, before)
-        lens = [L + 1 for L in lens]
-        sess.decode(i % layers, q, ids, lens, scale, out=o, ws=ws)
+            assert va.append_kv(layer, stream, knew, vnew, ids, cu, lens) == 0
+        lens[:] += 1
+        assert va.attn_decode(i % layers, stream, q, o, ids, lens, scale, ws, ws.numel()) == 0
+        # iteration boundary of the serving loop (Algorithm 1): the framework needs this iteration's
+        # output on the host before it can schedule the next one
+        torch_stream.synchronize()
+
+    def step_bytes():
+        return int(lens.sum()) * per_tok + qo_bytes
 
     for i in range(warmup):
         one_step(i)
     torch.cuda.synchronize()
-    sess.va.set_timing(True)
-    sess.va.kernel_time(0); sess.va.kernel_time(2)
     map0 = sess.va.counters()
     bytes_total = 0
     t0 = time.perf_counter()
     for i in range(steps):
         one_step(warmup + i)
-        bytes_total += _decode_bytes(shape, lens)
+        bytes_total += step_bytes()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    map1 = sess.va.counters()
+    # second pass, same steps again, with the library's per-launch HIP events switched on: the average
+    # launch duration of the split-K kernel (the event records perturb the whole-step time, so the
+    # two are measured separately)
+    sess.va.set_timing(True)
+    sess.va.kernel_time(0); sess.va.kernel_time(2)
+    kbytes = 0
+    ksteps = steps
+    for i in range(ksteps):
+        one_step(warmup + steps + i)
+        kbytes += step_bytes()
+    torch.cuda.synchronize()
     k_ms, k_n = sess.va.kernel_time(0)
     r_ms, r_n = sess.va.kernel_time(2)
     sess.va.set_timing(False)
-    map1 = sess.va.counters()
+    kbytes_per_launch = kbytes / max(k_n, 1)
     ms_per_step = (t1 - t0) * 1e3 / steps
     bytes_per_step = bytes_total / steps
     res = {
@@ -150,9 +175,10 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
         "gbs_step": bytes_per_step / (ms_per_step * 1e6),
         "kernel_ms": k_ms / max(k_n, 1),
         "reduce_ms": r_ms / max(r_n, 1),
-        "gbs_kernel": bytes_per_step / (k_ms / max(k_n, 1) * 1e6),
+        "gbs_kernel": kbytes_per_launch / (k_ms / max(k_n, 1) * 1e6),
         "bytes_per_step": bytes_per_step,
-        "tokens_in_batch": sum(lens),
+        "kbytes_per_launch": kbytes_per_launch,
+        "tokens_in_batch": int(lens.sum()),
         "map_calls_in_timed_region": map1[0] - map0[0],
         "map_us_in_timed_region": map1[2] - map0[2],
         "unmap_calls_in_timed_region": map1[1] - map0[1],
@@ -162,12 +188,12 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
         import numpy as np
         from oracle import attention as OA
 
-        last_layer = (warmup + steps - 1) % layers
+        last_layer = (warmup + 2 * steps - 1) % layers
         torch.cuda.synchronize()
         qb = tensor_to_bits(q)
         kb_new, vb_new = tensor_to_bits(knew), tensor_to_bits(vnew)
         ks, vs = [], []
-        grown = lens[0] - kv_lens[0]
+        grown = int(lens[0]) - kv_lens[0]
         for r in range(n):
             k0, v0 = host[r]
             ks.append(np.concatenate([tensor_to_bits(k0)] + [kb_new[r:r + 1]] * grown))
@@ -179,8 +205,8 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
         err = float(np.abs(got - want).max())
         rel = float((np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max())
         res["cpu_baseline"] = {
-            "value": _decode_bytes(shape, lens) / dt / 1e9, "unit": "GB/s", "cores": OA.num_threads(), "kind": "oracle",
-            "sample": f"the full decode batch of the last timed step once ({n} requests, {sum(lens)} tokens, layer {last_layer}): {dt:.2f} s",
+            "value": step_bytes() / dt / 1e9, "unit": "GB/s", "cores": OA.num_threads(), "kind": "oracle",
+            "sample": f"the full decode batch of the last timed step once ({n} requests, {int(lens.sum())} tokens, layer {last_layer}): {dt:.2f} s",
             "gpu_vs_oracle_max_abs": err, "gpu_vs_oracle_row_rel": rel,
         }
     sess.close()
@@ -241,9 +267,11 @@ def _measured_traffic(name):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", choices=["all", "decode", "prefill"], default="all")
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=300,
+                    help="untimed steps; the first ~50 ms of sustained load on a fresh process contain a one-off "
+                         "30-40 ms device stall (seen between two back-to-back launches), so keep this >= 200")
+    ap.add_argument("--only", choices=["all", "decode", "prefill", "copy"], default="all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -266,6 +294,17 @@ def main() -> int:
            "config": {"workload": "C2 Yi-6B-shaped decode: 64 requests, Hq=32 H=4 D=128, ctx U[1024,16384], "
                                   "one token per request per step (step + append_kv + split-K decode + reduce), 2 MiB page-groups"}}
     also = {}
+    if args.only == "copy":
+        # Calibration for the HBM-traffic counters: a plain device copy of known size (1 GiB read + 1 GiB
+        # written per launch), so that FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes.
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "torch device copy", "bytes_read_per_launch": n, "bytes_written_per_launch": n, "launches": 5}))
+        return 0
     if args.only in ("all", "decode"):
         wl = W.config(1)
         r = run_decode(args, torch, W, wl, args.steps, args.warmup, with_oracle=not args.no_cpu_baseline)
@@ -274,7 +313,7 @@ def main() -> int:
         out["pct_of_hbm_peak"] = 100.0 * r["gbs_step"] / HBM_PEAK_GBS
         out["roofline"] = {"kernel": "decode_splitk_kernel<128>", "bound": "hbm", "achieved": r["gbs_kernel"],
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": r["gbs_kernel"] / HBM_PEAK_GBS,
-                           "avg_launch_ms": r["kernel_ms"], "algorithmic_bytes_per_launch": r["bytes_per_step"],
+                           "avg_launch_ms": r["kernel_ms"], "algorithmic_bytes_per_launch": r["kbytes_per_launch"],
                            "traffic": _measured_traffic("decode_splitk_C2")}
         if "cpu_baseline" in r:
             out["cpu_baseline"] = r.pop("cpu_baseline")
@@ -290,7 +329,7 @@ def main() -> int:
                                         "traffic": _measured_traffic("prefill_C3")}
     if args.only == "all":
         wl4 = W.config(3)
-        d4 = run_decode(args, torch, W, wl4, max(10, args.steps // 5), 3, layers=1, with_oracle=False, churn=True)
+        d4 = run_decode(args, torch, W, wl4, max(10, args.steps // 10), 10, layers=1, with_oracle=False, churn=True)
         also["C4_yi34b_mixed_decode_part"] = {"gbs_step": d4["gbs_step"], "gbs_kernel": d4["gbs_kernel"],
                                               "frac_of_hbm_peak_kernel": d4["gbs_kernel"] / HBM_PEAK_GBS,
                                               "ms_per_step": d4["ms_per_step"], "kernel_ms": d4["kernel_ms"],
@@ -304,7 +343,7 @@ def main() -> int:
         also["C5_long_prefill_131072"] = {"kernel_tflops": p5["tflops_kernel"], "frac_of_bf16_mfma_peak": p5["frac_of_mfma_peak"],
                                           "kernel_ms": p5["kernel_ms"]}
         wl5d = W.Workload("C5-decode", wl5.shape, wl5.seed, [1], [131072])
-        d5 = run_decode(args, torch, W, wl5d, 64, 5, layers=2, with_oracle=False)
+        d5 = run_decode(args, torch, W, wl5d, 256, 50, layers=2, with_oracle=False)
         also["C5_long_decode_131072"] = {"gbs_kernel": d5["gbs_kernel"], "frac_of_hbm_peak_kernel": d5["gbs_kernel"] / HBM_PEAK_GBS,
                                          "kernel_ms": d5["kernel_ms"], "ms_per_step": d5["ms_per_step"]}
     if args.only == "prefill":

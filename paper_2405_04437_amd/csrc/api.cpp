@@ -161,7 +161,14 @@ int64_t vattn_decode_workspace_bytes(vattn_ctx* ctx, const int64_t* kv_lens, int
     if (!ctx || n < 0 || (n > 0 && !kv_lens)) { set_error("decode_workspace_bytes: invalid argument"); return -1; }
     for (int i = 0; i < n; ++i)
         if (kv_lens[i] < 1) { set_error("decode_workspace_bytes: context lengths must be >= 1"); return -1; }
-    return static_cast<int64_t>(decode_workspace_need(ctx, plan_decode(ctx, kv_lens, n), n));
+    DecodePlan p = plan_decode(ctx, kv_lens, n);
+    if (ctx->decode_chunk == 0) {
+        // In the balanced mode the segment count never exceeds the resident workgroup slots, whatever
+        // the lengths: size for that bound so that the same workspace serves the batch as it grows.
+        const int resident = decode_resident_workgroups(ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, ctx->cfg.head_dim, ctx->num_cus);
+        p.num_segs = resident * ctx->decode_oversub;
+    }
+    return static_cast<int64_t>(decode_workspace_need(ctx, p, n));
 }
 
 int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,

@@ -336,15 +336,19 @@ bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t
     const int waves = waves_per_workgroup(a.Hq, a.H);
     dim3 grid(static_cast<unsigned>(a.num_segs), static_cast<unsigned>((units + waves - 1) / waves));
     dim3 block(static_cast<unsigned>(waves * 64));
-    auto launch = [&](auto kernel, size_t wave_lds) -> bool {
-        // dynamic LDS above 64 KiB has to be allowed per kernel; the call is cheap and idempotent
-        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxWaves * wave_lds)), "hipFuncSetAttribute")) return false;
+    static bool allowed[4] = {false, false, false, false};  // per kernel variant
+    auto launch = [&](auto kernel, size_t wave_lds, int variant) -> bool {
+        // dynamic LDS above 64 KiB has to be allowed once per kernel
+        if (!allowed[variant]) {
+            if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxWaves * wave_lds)), "hipFuncSetAttribute")) return false;
+            allowed[variant] = true;
+        }
         hipLaunchKernelGGL(kernel, grid, block, static_cast<size_t>(waves) * wave_lds, stream, a, units, hb_per_kv, meta);
         return true;
     };
     bool ok;
-    if (a.D == 128) ok = a.inline_meta ? launch(decode_splitk_kernel<128, true>, Geo<128>::WAVE_LDS) : launch(decode_splitk_kernel<128, false>, Geo<128>::WAVE_LDS);
-    else ok = a.inline_meta ? launch(decode_splitk_kernel<64, true>, Geo<64>::WAVE_LDS) : launch(decode_splitk_kernel<64, false>, Geo<64>::WAVE_LDS);
+    if (a.D == 128) ok = a.inline_meta ? launch(decode_splitk_kernel<128, true>, Geo<128>::WAVE_LDS, 0) : launch(decode_splitk_kernel<128, false>, Geo<128>::WAVE_LDS, 1);
+    else ok = a.inline_meta ? launch(decode_splitk_kernel<64, true>, Geo<64>::WAVE_LDS, 2) : launch(decode_splitk_kernel<64, false>, Geo<64>::WAVE_LDS, 3);
     if (!ok) return false;
     return hip_ok(hipGetLastError(), "decode split-K launch");
 }

@@ -323,15 +323,18 @@ bool launch_prefill(const PrefillArgs& a_in, hipStream_t stream) {
     if (grid.x == 0) return true;
     PrefillArgs a = a_in;
     { const char* e = getenv("VATTN_PREFILL_DBG"); a.dbg = e ? atoi(e) : 0; }
-    auto launch = [&](auto kernel, int lds) -> bool {
-        // dynamic LDS above 64 KiB has to be allowed per kernel; the call is cheap and idempotent
-        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds), "hipFuncSetAttribute")) return false;
+    static bool allowed[4] = {false, false, false, false};  // per kernel variant
+    auto launch = [&](auto kernel, int lds, int variant) -> bool {
+        if (!allowed[variant]) {  // dynamic LDS above 64 KiB has to be allowed once per kernel
+            if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds), "hipFuncSetAttribute")) return false;
+            allowed[variant] = true;
+        }
         hipLaunchKernelGGL(kernel, grid, dim3(kThreads), static_cast<size_t>(lds), stream, a);
         return true;
     };
     bool ok;
-    if (prefill_qb() == 2) ok = a.D == 128 ? launch(prefill_kernel<128, 2>, PGeo<128>::LDS) : launch(prefill_kernel<64, 2>, PGeo<64>::LDS);
-    else ok = a.D == 128 ? launch(prefill_kernel<128, 1>, PGeo<128>::LDS) : launch(prefill_kernel<64, 1>, PGeo<64>::LDS);
+    if (prefill_qb() == 2) ok = a.D == 128 ? launch(prefill_kernel<128, 2>, PGeo<128>::LDS, 0) : launch(prefill_kernel<64, 2>, PGeo<64>::LDS, 1);
+    else ok = a.D == 128 ? launch(prefill_kernel<128, 1>, PGeo<128>::LDS, 2) : launch(prefill_kernel<64, 1>, PGeo<64>::LDS, 3);
     if (!ok) return false;
     return hip_ok(hipGetLastError(), "prefill launch");
 }
