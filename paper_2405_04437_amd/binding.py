@@ -58,9 +58,10 @@ def _load() -> ctypes.CDLL:
     lib.vattn_kernel_time.argtypes = [vp, ctypes.c_int, dp, i64p]
     lib.vattn_set_decode_chunk.argtypes = [vp, ctypes.c_int]
     lib.vattn_set_decode_tuning.argtypes = [vp, ctypes.c_int]
+    lib.vattn_set_prefill_wide.argtypes = [vp, ctypes.c_int]
     for name in ("vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_query",
                  "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill", "vattn_attn_decode",
-                 "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning"):
+                 "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -70,7 +71,7 @@ lib = _load()
 EXPORTED = ["vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_kv_ptr",
             "vattn_query", "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill",
             "vattn_decode_workspace_bytes", "vattn_attn_decode", "vattn_set_timing", "vattn_kernel_time",
-            "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_last_error"]
+            "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide", "vattn_last_error"]
 
 
 def last_error() -> str:
@@ -185,6 +186,9 @@ class Vattn:
 
     def set_decode_chunk(self, tokens: int) -> int:
         return lib.vattn_set_decode_chunk(self._h, tokens)
+
+    def set_prefill_wide(self, enabled: bool) -> int:
+        return lib.vattn_set_prefill_wide(self._h, 1 if enabled else 0)
 
     def set_decode_tuning(self, segments_per_slot: int) -> int:
         return lib.vattn_set_decode_tuning(self._h, segments_per_slot)

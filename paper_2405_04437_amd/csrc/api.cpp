@@ -235,7 +235,10 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
     if (n == 0) return 0;
     if (cu_q[0] != 0) { set_error("attn_prefill: cu_q[0] must be 0"); return -1; }
     const int H = ctx->cfg.num_kv_heads, Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
-    const int BM = prefill_tile_rows(Hq, H, D);
+    // 128 query rows per work item by default; the wide kernel (256 rows, one workgroup per CU,
+    // software-pipelined) is opt-in: measured equal on long prompts and slower on short ones.
+    const bool wide = ctx->prefill_wide;
+    const int BM = wide ? 256 : 128;
     for (int r = 0; r < n; ++r) {
         const int64_t ql = static_cast<int64_t>(cu_q[r + 1]) - cu_q[r];
         if (ql < 0) { set_error("attn_prefill: cu_q must be non-decreasing"); return -1; }
@@ -293,7 +296,7 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
     a.items = reinterpret_cast<const PrefillItem*>(d + off_items);
     a.items_per_xcd = static_cast<int>(per_xcd); a.n = n; a.scale = scale;
     if (ctx->timing && !ctx->timers[1].begin(s)) return -1;
-    if (!launch_prefill(a, s)) return -1;
+    if (!(wide ? launch_prefill_wide(a, s) : launch_prefill(a, s))) return -1;
     if (ctx->timing && !ctx->timers[1].end(s)) return -1;
     return 0;
 }
@@ -312,6 +315,12 @@ int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* laun
 int vattn_set_decode_chunk(vattn_ctx* ctx, int tokens) {
     if (!ctx || tokens < 0 || tokens % 32 != 0) { set_error("set_decode_chunk: tokens must be a non-negative multiple of 32"); return -1; }
     ctx->decode_chunk = tokens;
+    return 0;
+}
+
+int vattn_set_prefill_wide(vattn_ctx* ctx, int enabled) {
+    if (!ctx) { set_error("set_prefill_wide: null context"); return -1; }
+    ctx->prefill_wide = enabled != 0;
     return 0;
 }
 

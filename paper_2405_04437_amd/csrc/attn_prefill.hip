@@ -18,8 +18,6 @@
 //    and share the K/V stream through that XCD's L2.
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
-
 #include "vattn_internal.h"
 
 namespace vattn {
@@ -55,14 +53,10 @@ template <int D> struct PGeo {
     static constexpr int LDS = 2 * BUF;
 };
 
-// QB = 32-row query blocks per wave.  With QB = 2 every K and V fragment read from LDS feeds two
-// multiplies (one per query block), which halves the LDS traffic per flop - with QB = 1 the LDS would
-// have to deliver 128 B/clk/CU at the matrix peak, i.e. all it has - and a workgroup covers 256 query
-// rows, halving the K/V bytes each CU pulls from L2.  QB = 2 needs one wave per SIMD (about 400
-// registers); QB = 1 is kept for short prompts, where more, smaller work items balance better.
-template <int D, int QB>
-__global__ __launch_bounds__(kThreads, (QB == 1 ? 2 : 1)) void prefill_kernel(PrefillArgs a) {
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
     using G = PGeo<D>;
+    constexpr int QB = 1;                      // 32-row query blocks per wave (the wide kernel has two)
     constexpr int BM = 128 * QB;               // query rows per workgroup
     constexpr int WR = 32 * QB;                // query rows per wave
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -70,7 +64,6 @@ __global__ __launch_bounds__(kThreads, (QB == 1 ? 2 : 1)) void prefill_kernel(Pr
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform per wave: keeps row/tile arithmetic scalar
     const int l = tid & 63;
     const int group = a.Hq / a.H;
-    const int dbg = a.dbg;
 
     // work item: queue of this XCD, slot bid/8; the heads of a group are adjacent slots
     const int xcd = blockIdx.x & 7;
@@ -211,7 +204,6 @@ __global__ __launch_bounds__(kThreads, (QB == 1 ? 2 : 1)) void prefill_kernel(Pr
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[qa][tb][i]);
             mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;   // scale > 0: max commutes with scaling
-            if (dbg & 16) mx = 0.f;
             // Rows past q_len are clamped copies of the last row, and key 0 is visible to every row, so
             // the first tile always raises m from -inf to a finite value for all lanes.
             if (__builtin_amdgcn_ballot_w64(mx > m[qa] + kLazy) != 0) {
@@ -283,11 +275,11 @@ __global__ __launch_bounds__(kThreads, (QB == 1 ? 2 : 1)) void prefill_kernel(Pr
         for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(qb[qa][ks]));
 
     for (int t = 0; t < ntiles; ++t) {
-        if (wave_active(t) && !(dbg & 1)) tile_scores(t);
-        if (!(dbg & 4)) issue_loads(kregA, vregA, t + 1);
-        if (wave_active(t) && !(dbg & 2)) tile_softmax_pv(t);
-        if (!(dbg & 4)) store_tile(kregA, vregA, (t + 1) & 1);
-        if (!(dbg & 8)) __syncthreads();
+        if (wave_active(t)) tile_scores(t);
+        issue_loads(kregA, vregA, t + 1);
+        if (wave_active(t)) tile_softmax_pv(t);
+        store_tile(kregA, vregA, (t + 1) & 1);
+        __syncthreads();
     }
 
 #pragma unroll
@@ -312,18 +304,12 @@ __global__ __launch_bounds__(kThreads, (QB == 1 ? 2 : 1)) void prefill_kernel(Pr
 
 }  // namespace
 
-// Query rows per work item: 128 (one 32-row block per wave); VATTN_PREFILL_QB=2 selects the 256-row variant.
-static int prefill_qb() { static const int qb = [] { const char* e = getenv("VATTN_PREFILL_QB"); return e && atoi(e) == 2 ? 2 : 1; }(); return qb; }
-int prefill_tile_rows(int, int, int) { return 128 * prefill_qb(); }
-int prefill_heads_per_item(int Hq, int H, int) { return Hq / H; }
-
 bool launch_prefill(const PrefillArgs& a_in, hipStream_t stream) {
     const int group = a_in.Hq / a_in.H;
     dim3 grid(static_cast<unsigned>(8 * a_in.items_per_xcd * group));
     if (grid.x == 0) return true;
-    PrefillArgs a = a_in;
-    { const char* e = getenv("VATTN_PREFILL_DBG"); a.dbg = e ? atoi(e) : 0; }
-    static bool allowed[4] = {false, false, false, false};  // per kernel variant
+    const PrefillArgs& a = a_in;
+    static bool allowed[2] = {false, false};  // per kernel variant
     auto launch = [&](auto kernel, int lds, int variant) -> bool {
         if (!allowed[variant]) {  // dynamic LDS above 64 KiB has to be allowed once per kernel
             if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds), "hipFuncSetAttribute")) return false;
@@ -332,10 +318,7 @@ bool launch_prefill(const PrefillArgs& a_in, hipStream_t stream) {
         hipLaunchKernelGGL(kernel, grid, dim3(kThreads), static_cast<size_t>(lds), stream, a);
         return true;
     };
-    bool ok;
-    if (prefill_qb() == 2) ok = a.D == 128 ? launch(prefill_kernel<128, 2>, PGeo<128>::LDS, 0) : launch(prefill_kernel<64, 2>, PGeo<64>::LDS, 1);
-    else ok = a.D == 128 ? launch(prefill_kernel<128, 1>, PGeo<128>::LDS, 2) : launch(prefill_kernel<64, 1>, PGeo<64>::LDS, 3);
-    if (!ok) return false;
+    if (!(a.D == 128 ? launch(prefill_kernel<128>, PGeo<128>::LDS, 0) : launch(prefill_kernel<64>, PGeo<64>::LDS, 1))) return false;
     return hip_ok(hipGetLastError(), "prefill launch");
 }
 

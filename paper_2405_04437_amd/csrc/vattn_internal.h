@@ -135,11 +135,11 @@ struct PrefillArgs {
     const PrefillItem* items;               // device: 8 queues of items_per_xcd entries each
     int items_per_xcd; int n;
     float scale;
-    int dbg;
 };
-int prefill_tile_rows(int Hq, int H, int D);     // query positions covered by one work item
-int prefill_heads_per_item(int Hq, int H, int D);
+// Two kernels: 128 query rows per work item (two workgroups per CU), and a wide one with 256 rows per
+// work item for long prompts (one workgroup per CU, software-pipelined).
 bool launch_prefill(const PrefillArgs& a, hipStream_t stream);
+bool launch_prefill_wide(const PrefillArgs& a, hipStream_t stream);
 
 }  // namespace vattn
 
@@ -151,5 +151,6 @@ struct vattn_ctx {
     bool timing = false;
     int decode_chunk = 0;
     int decode_oversub = 1;  // segments per resident workgroup slot
+    bool prefill_wide = false;
     int num_cus = 0;
 };
