@@ -118,26 +118,26 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
 
     const int ld_row = l / G::LPR;            // row inside one load instruction
     const int ld_col = (l % G::LPR) * 16;     // byte offset inside the row
+    const int lane_off = ld_row * static_cast<int>(row_stride) + ld_col;
     u32x4 kreg[G::NL], vreg[G::NL];
     // K and V of this (request, KV head) as raw buffer resources: the loads then take one 32-bit
     // per-lane offset plus a scalar offset, so all tile/row address arithmetic runs on the scalar unit.
-    // num_records ends at the last valid row of this head: the hardware range check is a second guard
-    // behind the explicit clamp below (out-of-range buffer reads return zero instead of faulting).
+    // num_records ends at the last valid row of this head: reads beyond it are suppressed by the
+    // hardware range check and return zero.
     const int nrec = (kv_len - 1) * static_cast<int>(row_stride) + G::RB;
     const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kp), 0, nrec, kRsrcWord3);
     const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vp), 0, nrec, kRsrcWord3);
     auto issue_loads = [&](u32x4 (&kreg)[G::NL], u32x4 (&vreg)[G::NL], int t) {
-        // Rows past the end of the context (ragged last tile) are clamped to the last valid token, so
-        // nothing beyond what step() has mapped is ever read; their scores are masked below.  The clamp
-        // is branch-free (a few VALU ops per tile) so that the load/wait order stays static.
-        const int first = tok0 + t * kTile;
-        const int sbase = first * static_cast<int>(row_stride);
-        const int last = kv_len - 1 - first;
+        // One per-lane offset for the whole kernel plus a scalar offset per load instruction.  Rows past
+        // the end of the context (ragged last tile) lie beyond num_records: the hardware range check
+        // returns zeros for them and touches nothing, so no byte beyond what step() has mapped is read;
+        // their scores are masked below.
+        const int sbase = (tok0 + t * kTile) * static_cast<int>(row_stride);
 #pragma unroll
         for (int i = 0; i < G::NL; ++i) {
-            const int off = min(i * G::RPI + ld_row, last) * static_cast<int>(row_stride) + ld_col;
-            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, off, sbase, kAuxNt);
-            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, off, sbase, kAuxNt);
+            const int so = sbase + i * G::RPI * static_cast<int>(row_stride);
+            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, lane_off, so, kAuxNt);
+            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, lane_off, so, kAuxNt);
         }
     };
     auto stage = [&](const u32x4 (&kreg)[G::NL], const u32x4 (&vreg)[G::NL]) {

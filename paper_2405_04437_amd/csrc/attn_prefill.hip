@@ -104,19 +104,22 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
 
     const int ld_row = tid / G::LPR;
     const int ld_col = (tid % G::LPR) * 16;
+    // Global addressing: one per-lane offset for the whole kernel + a scalar offset per load.  Rows past
+    // the end of the context lie beyond num_records; the hardware range check returns zeros for them and
+    // touches nothing, so no byte beyond what step() has mapped is read (their scores are masked).
+    const int lane_off = ld_row * rs32 + ld_col;
     // One register set stages the next tile: it is requested right after the score multiplies of tile t
     // have been issued and written to the other LDS buffer at the end of the iteration.  The issue is
-    // unconditional (rows are clamped to the last token of the context, so a tile index past the end
-    // just re-reads that token) and sits at one place in the loop, which lets the compiler keep the
-    // loads in flight across the softmax and the second contraction.
+    // unconditional (a tile index past the end is out of range for every lane and loads zeros without
+    // touching memory) and sits at one place in the loop, which lets the compiler keep the loads in
+    // flight across the softmax and the second contraction.
     u32x4 kregA[G::NL], vregA[G::NL];
     auto issue_loads = [&](u32x4 (&kreg)[G::NL], u32x4 (&vreg)[G::NL], int t) {
 #pragma unroll
         for (int i = 0; i < G::NL; ++i) {
-            const int tok = min(t * kBN + i * G::RPI + ld_row, kv_len - 1);  // never beyond the mapped context
-            const int voff = static_cast<int>(__umul24(tok, rs32)) + ld_col;
-            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, voff, 0, 0);
-            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, voff, 0, 0);
+            const int so = (t * kBN + i * G::RPI) * rs32;   // scalar; rows past the context are out of range
+            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, lane_off, so, 0);
+            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, lane_off, so, 0);
         }
     };
     auto store_tile = [&](const u32x4 (&kreg)[G::NL], const u32x4 (&vreg)[G::NL], int buf) {
@@ -204,7 +207,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[qa][tb][i]);
             mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;   // scale > 0: max commutes with scaling
-            // Rows past q_len are clamped copies of the last row, and key 0 is visible to every row, so
+            // Query rows past q_len hold a copy of the last row's Q, and key 0 is visible to every row, so
             // the first tile always raises m from -inf to a finite value for all lanes.
             if (__builtin_amdgcn_ballot_w64(mx > m[qa] + kLazy) != 0) {
                 const float m_new = fmaxf(m[qa], mx);

@@ -4,19 +4,19 @@
 // from the request's virtually contiguous sub-tensor), arranged for long prompts:
 //
 //  * Each wave owns two 32-row query blocks, so every K and V fragment read from LDS feeds two
-//    v_mfma_f32_32x32x16_bf16 instead of one.  With one block per wave the LDS would have to deliver
-//    128 B/clk/CU at the matrix peak - all it has; with two it is half of that, and a 256-row workgroup
-//    also halves the K/V bytes each CU pulls through L2.
+//    v_mfma_f32_32x32x16_bf16 instead of one.  With one block per wave the LDS has to deliver about
+//    128 B/clk/CU at the matrix peak, more than half of the ~215 B/clk measured for it; with two it is
+//    half of that, and a 256-row workgroup also halves the K/V bytes each CU pulls through L2.
 //  * The price is registers (two output accumulators, two Q fragment sets): one wave per SIMD.  With no
 //    second wave to hide behind, matrix and vector work are interleaved inside the wave: the KV sequence
 //    is walked in half-steps of 32 tokens, and while the score multiplies of half-step h+1 are in the
 //    matrix pipe the vector unit does the softmax of half-step h (software pipeline, scores ping-pong
 //    between two register sets).  The pipelined loop covers the half-steps that lie entirely below the
 //    workgroup's diagonal; the few diagonal half-steps run through a plain masked path.
-//  * K/V tiles of 64 tokens sit in a four-stage LDS ring: tile T+2 is requested from global memory at
-//    the start of tile T, written to LDS at its end, and first read one tile later; the second
-//    contraction runs one half-step behind the scores, so tile T-1 is still being read during tile T.
-//    One workgroup barrier per tile.
+//  * K/V tiles of 64 tokens sit in a three-stage LDS ring: tile T+2 is requested from global memory at
+//    the start of tile T and written to LDS at its end, into the stage tile T-1 was read from (that
+//    iteration ended with a barrier).  During tile T the waves read tile T and, for the scores that run
+//    one half-step ahead, the first half of tile T+1.  One workgroup barrier per tile.
 #include <hip/hip_runtime.h>
 
 #include "vattn_internal.h"
@@ -104,14 +104,17 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_wide_kernel(PrefillArgs a
 
     const int ld_row = tid / G::LPR;
     const int ld_col = (tid % G::LPR) * 16;
+    // Global addressing: one per-lane offset for the whole kernel + a scalar offset per load.  Rows past
+    // the end of the context lie beyond num_records; the hardware range check returns zeros for them and
+    // touches nothing, so no byte beyond what step() has mapped is read (their scores are masked).
+    const int lane_off = ld_row * rs32 + ld_col;
     u32x4 kreg[G::NL], vreg[G::NL];
     auto issue_loads = [&](int T) {
 #pragma unroll
         for (int i = 0; i < G::NL; ++i) {
-            const int tok = min(T * kTile + i * G::RPI + ld_row, kv_len - 1);  // never beyond the mapped context
-            const int voff = static_cast<int>(__umul24(tok, rs32)) + ld_col;
-            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, voff, 0, 0);
-            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, voff, 0, 0);
+            const int so = (T * kTile + i * G::RPI) * rs32;   // scalar; rows past the context are out of range
+            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, lane_off, so, 0);
+            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, lane_off, so, 0);
         }
     };
     auto store_tile = [&](int stage) {

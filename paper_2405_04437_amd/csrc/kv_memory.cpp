@@ -60,6 +60,7 @@ bool KvMemory::init(const vattn_config& c) {
     N_ = c.num_layers; B_ = c.max_batch; L_ = c.max_ctx; policy_ = c.flags; G_ = G;
     T_ = static_cast<int64_t>(c.num_kv_heads) * c.head_dim * c.elem_bytes;
     S_ = (L_ * T_ + G_ - 1) / G_ * G_;
+    if (S_ >= (int64_t{1} << 31)) { set_error("init: one request's sub-tensor (L*H*D*P) must stay below 2 GiB (32-bit buffer offsets in the kernels)"); return false; }
     pool_total_ = c.phys_budget_bytes / G_;
     if (pool_total_ < 0) { set_error("init: negative physical budget"); return false; }
 
