@@ -142,10 +142,12 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q /*d
 
 /* ---- measurement helpers --------------------------------------------------------------------- */
 
-/* When enabled, every launch of the split-K decode kernel and of the prefill kernel is bracketed
- * by HIP events on the launch stream; vattn_kernel_time() then synchronises those events and
- * returns the accumulated kernel time in milliseconds and the number of launches since the last
- * call, per kernel (which: 0 = decode split-K, 1 = prefill, 2 = decode reduce), and resets them. */
+/* When enabled, every launch of the split-K decode kernel, the reduce kernel and the prefill kernel
+ * carries a pair of HIP events that the launch stream records when the kernel starts and when it
+ * ends (hipExtLaunchKernelGGL), so their distance is the kernel's execution time without launch
+ * gaps; vattn_kernel_time() then synchronises those events and returns the accumulated kernel time
+ * in milliseconds and the number of launches since the last call, per kernel (which: 0 = decode
+ * split-K, 1 = prefill, 2 = decode reduce), and resets them. */
 int vattn_set_timing(vattn_ctx* ctx, int enabled);
 int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* launches);
 

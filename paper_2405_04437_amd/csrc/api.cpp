@@ -219,12 +219,10 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, vo
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + part_o_bytes);
     const InlineMeta* imp = inl ? &im : nullptr;
-    if (ctx->timing && !ctx->timers[0].begin(s)) return -1;
-    if (!launch_decode_splitk(a, imp, s)) return -1;
-    if (ctx->timing && !ctx->timers[0].end(s)) return -1;
-    if (ctx->timing && !ctx->timers[2].begin(s)) return -1;
-    if (!launch_decode_reduce(a, imp, s)) return -1;
-    if (ctx->timing && !ctx->timers[2].end(s)) return -1;
+    LaunchEvents ev_split, ev_reduce;
+    if (ctx->timing && (!ctx->timers[0].next(&ev_split.start, &ev_split.stop) || !ctx->timers[2].next(&ev_reduce.start, &ev_reduce.stop))) return -1;
+    if (!launch_decode_splitk(a, imp, s, ev_split)) return -1;
+    if (!launch_decode_reduce(a, imp, s, ev_reduce)) return -1;
     return 0;
 }
 
@@ -295,9 +293,9 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
     a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
     a.items = reinterpret_cast<const PrefillItem*>(d + off_items);
     a.items_per_xcd = static_cast<int>(per_xcd); a.n = n; a.scale = scale;
-    if (ctx->timing && !ctx->timers[1].begin(s)) return -1;
-    if (!(wide ? launch_prefill_wide(a, s) : launch_prefill(a, s))) return -1;
-    if (ctx->timing && !ctx->timers[1].end(s)) return -1;
+    LaunchEvents ev;
+    if (ctx->timing && !ctx->timers[1].next(&ev.start, &ev.stop)) return -1;
+    if (!(wide ? launch_prefill_wide(a, s, ev) : launch_prefill(a, s, ev))) return -1;
     return 0;
 }
 

@@ -24,6 +24,7 @@
 //    re-read as 16-byte A operands, V is re-read with the transposing LDS load ds_read_b64_tr_b16,
 //    which delivers "8 tokens of one channel" per lane as the A operand of O^T = V^T P^T.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include "vattn_internal.h"
 
@@ -328,7 +329,7 @@ int decode_resident_workgroups(int Hq, int H, int D, int num_cus) {
     return segs > 0 ? segs : 1;
 }
 
-bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream) {
+bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev) {
     const InlineMeta& meta = im ? *im : kNoInline;
     const int group = a.Hq / a.H;
     const int hb_per_kv = (group + 15) / 16;
@@ -343,7 +344,7 @@ bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t
             if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxWaves * wave_lds)), "hipFuncSetAttribute")) return false;
             allowed[variant] = true;
         }
-        hipLaunchKernelGGL(kernel, grid, block, static_cast<size_t>(waves) * wave_lds, stream, a, units, hb_per_kv, meta);
+        hipExtLaunchKernelGGL(kernel, grid, block, static_cast<size_t>(waves) * wave_lds, stream, ev.start, ev.stop, 0, a, units, hb_per_kv, meta);
         return true;
     };
     bool ok;
@@ -353,16 +354,16 @@ bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t
     return hip_ok(hipGetLastError(), "decode split-K launch");
 }
 
-bool launch_decode_reduce(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream) {
+bool launch_decode_reduce(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev) {
     const InlineMeta& meta = im ? *im : kNoInline;
     dim3 grid(static_cast<unsigned>(a.n * a.Hq));
     const dim3 block(kReduceWaves * 64);
     if (a.D == 128) {
-        if (a.inline_meta) hipLaunchKernelGGL((decode_reduce_kernel<128, true>), grid, block, 0, stream, a, meta);
-        else hipLaunchKernelGGL((decode_reduce_kernel<128, false>), grid, block, 0, stream, a, meta);
+        if (a.inline_meta) hipExtLaunchKernelGGL((decode_reduce_kernel<128, true>), grid, block, 0, stream, ev.start, ev.stop, 0, a, meta);
+        else hipExtLaunchKernelGGL((decode_reduce_kernel<128, false>), grid, block, 0, stream, ev.start, ev.stop, 0, a, meta);
     } else {
-        if (a.inline_meta) hipLaunchKernelGGL((decode_reduce_kernel<64, true>), grid, block, 0, stream, a, meta);
-        else hipLaunchKernelGGL((decode_reduce_kernel<64, false>), grid, block, 0, stream, a, meta);
+        if (a.inline_meta) hipExtLaunchKernelGGL((decode_reduce_kernel<64, true>), grid, block, 0, stream, ev.start, ev.stop, 0, a, meta);
+        else hipExtLaunchKernelGGL((decode_reduce_kernel<64, false>), grid, block, 0, stream, ev.start, ev.stop, 0, a, meta);
     }
     return hip_ok(hipGetLastError(), "decode reduce launch");
 }

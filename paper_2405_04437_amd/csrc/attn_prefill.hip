@@ -17,6 +17,7 @@
 //    query heads of a group and neighbouring query tiles then run on the same XCD at the same time
 //    and share the K/V stream through that XCD's L2.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include "vattn_internal.h"
 
@@ -307,7 +308,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
 
 }  // namespace
 
-bool launch_prefill(const PrefillArgs& a_in, hipStream_t stream) {
+bool launch_prefill(const PrefillArgs& a_in, hipStream_t stream, LaunchEvents ev) {
     const int group = a_in.Hq / a_in.H;
     dim3 grid(static_cast<unsigned>(8 * a_in.items_per_xcd * group));
     if (grid.x == 0) return true;
@@ -318,7 +319,7 @@ bool launch_prefill(const PrefillArgs& a_in, hipStream_t stream) {
             if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds), "hipFuncSetAttribute")) return false;
             allowed[variant] = true;
         }
-        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), static_cast<size_t>(lds), stream, a);
+        hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), static_cast<size_t>(lds), stream, ev.start, ev.stop, 0, a);
         return true;
     };
     if (!(a.D == 128 ? launch(prefill_kernel<128>, PGeo<128>::LDS, 0) : launch(prefill_kernel<64>, PGeo<64>::LDS, 1))) return false;

@@ -18,6 +18,7 @@
 //    iteration ended with a barrier).  During tile T the waves read tile T and, for the scores that run
 //    one half-step ahead, the first half of tile T+1.  One workgroup barrier per tile.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include "vattn_internal.h"
 
@@ -362,7 +363,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_wide_kernel(PrefillArgs a
 
 }  // namespace
 
-bool launch_prefill_wide(const PrefillArgs& a, hipStream_t stream) {
+bool launch_prefill_wide(const PrefillArgs& a, hipStream_t stream, LaunchEvents ev) {
     const int group = a.Hq / a.H;
     dim3 grid(static_cast<unsigned>(8 * a.items_per_xcd * group));
     if (grid.x == 0) return true;
@@ -372,7 +373,7 @@ bool launch_prefill_wide(const PrefillArgs& a, hipStream_t stream) {
             if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds), "hipFuncSetAttribute")) return false;
             allowed[variant] = true;
         }
-        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), static_cast<size_t>(lds), stream, a);
+        hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), static_cast<size_t>(lds), stream, ev.start, ev.stop, 0, a);
         return true;
     };
     if (!(a.D == 128 ? launch(prefill_wide_kernel<128>, WGeo<128>::LDS, 0) : launch(prefill_wide_kernel<64>, WGeo<64>::LDS, 1))) return false;

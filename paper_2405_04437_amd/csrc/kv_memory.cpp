@@ -249,7 +249,7 @@ bool MetaRing::commit(size_t bytes, hipStream_t stream) {
 
 // ---------------------------------------------------------------------------------------------
 
-bool KernelTimer::begin(hipStream_t s) {
+bool KernelTimer::next(hipEvent_t* start, hipEvent_t* stop) {
     Pair p{};
     if (!spare.empty()) { p = spare.back(); spare.pop_back(); }
     else {
@@ -257,9 +257,9 @@ bool KernelTimer::begin(hipStream_t s) {
         if (!hip_ok(hipEventCreate(&p.b), "hipEventCreate")) return false;
     }
     open.push_back(p);
-    return hip_ok(hipEventRecord(p.a, s), "hipEventRecord");
+    *start = p.a; *stop = p.b;
+    return true;
 }
-bool KernelTimer::end(hipStream_t s) { return hip_ok(hipEventRecord(open.back().b, s), "hipEventRecord"); }
 bool KernelTimer::collect(double* total_ms, int64_t* launches) {
     double t = 0;
     for (auto& p : open) {

@@ -82,8 +82,9 @@ struct KernelTimer {
     struct Pair { hipEvent_t a, b; };
     std::vector<Pair> open;    // recorded, not yet read
     std::vector<Pair> spare;   // reusable events
-    bool begin(hipStream_t s);
-    bool end(hipStream_t s);
+    // Hands out the event pair of the next launch; the launcher attaches both to the kernel's dispatch,
+    // so their distance is the kernel's own execution time (no launch gaps, no neighbouring commands).
+    bool next(hipEvent_t* start, hipEvent_t* stop);
     bool collect(double* total_ms, int64_t* launches);
     void destroy();
 };
@@ -91,6 +92,8 @@ struct KernelTimer {
 // ---------------------------------------------------------------------------------------------
 // Kernel launchers (one per .hip file).  All pointers are device pointers.
 // ---------------------------------------------------------------------------------------------
+// Optional events recorded at the start and at the end of the kernel itself (both null: not timed).
+struct LaunchEvents { hipEvent_t start = nullptr; hipEvent_t stop = nullptr; };
 // Small index arrays travel inside the kernel-argument segment (no upload, no staging buffer) when
 // they fit; larger batches go through the pinned staging ring and are read through pointers.
 constexpr int kInlineMaxReq = 256;
@@ -123,8 +126,8 @@ struct DecodeArgs {
     int inline_meta; // 1: arrays are in InlineMeta as [reqids | kv_lens | cu_tiles]
 };
 int decode_resident_workgroups(int Hq, int H, int D, int num_cus);  // workgroups one launch keeps resident
-bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream);
-bool launch_decode_reduce(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream);
+bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});
+bool launch_decode_reduce(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});
 
 struct PrefillItem { int32_t req; int32_t kvh; int32_t q_tile; int32_t pad; };
 struct PrefillArgs {
@@ -138,8 +141,8 @@ struct PrefillArgs {
 };
 // Two kernels: 128 query rows per work item (two workgroups per CU), and a wide one with 256 rows per
 // work item for long prompts (one workgroup per CU, software-pipelined).
-bool launch_prefill(const PrefillArgs& a, hipStream_t stream);
-bool launch_prefill_wide(const PrefillArgs& a, hipStream_t stream);
+bool launch_prefill(const PrefillArgs& a, hipStream_t stream, LaunchEvents ev = {});
+bool launch_prefill_wide(const PrefillArgs& a, hipStream_t stream, LaunchEvents ev = {});
 
 }  // namespace vattn
 
