@@ -165,3 +165,135 @@ def test_conservation_on_a_random_trace():
                     assert all(m.mapped[r] >= m.need(lens[r]) for r in range(8) if m.active[r])
             assert sum(m.mapped) * 2 * m.N + m.pool_free == m.pool_total
             assert m.pool_free >= 0
+
+
+# ---- tensor slicing (Discussion section of the paper) ---------------------------------------------
+
+def test_tokens_per_page_with_tensor_slicing_table():
+    for model, tp, heads, without, with_, exact in _rows("tokens_per_page_sliced.txt"):
+        sh = SHAPES[model]
+        plain = AllocatorModel(sh.num_layers, 4, 4096, int(heads), sh.head_dim, 2, 2 * MiB, 0)
+        sliced = AllocatorModel(sh.num_layers, 4, 4096, int(heads), sh.head_dim, 2, 2 * MiB, 0, sliced=True)
+        assert plain.tokens_per_page_group() == int(without)
+        quotient = 2 * MiB / (sh.num_layers * int(heads) * sh.head_dim * 2)
+        if int(exact):
+            assert sliced.tokens_per_page_group() == int(with_) == quotient
+        else:  # printed: the TP-1 quotient rounded up (doubled for TP-2); whole tokens per page is the floor
+            assert int(tp) * int(np.ceil(quotient / int(tp))) == int(with_)
+            assert sliced.tokens_per_page_group() == int(np.floor(quotient))
+        # fragmentation falls to 1/N of the unsliced design (up to the floor)
+        assert plain.tokens_per_page_group() // sh.num_layers == sliced.tokens_per_page_group()
+        t = sliced.tokens_per_page_group()
+        assert sliced.need(t) == 1 and sliced.need(t + 1) == 2
+
+
+def test_sliced_growth_takes_two_handles_per_page_group_and_same_bytes():
+    N, H, D = 32, 8, 128
+    plain = AllocatorModel(N, 2, 8192, H, D, 2, 2 * MiB, 10 ** 6)
+    sliced = AllocatorModel(N, 2, 8192, H, D, 2, 2 * MiB, 10 ** 6, sliced=True)
+    for m in (plain, sliced):
+        r = m.alloc_reqid()
+        assert m.step([8192, 0]) == 0
+    # same physical bytes for a full-length request, N times fewer bytes for a one-token request
+    assert plain.map_calls == sliced.map_calls == 2 * N * 8192 * H * D * 2 // (2 * MiB)
+    assert sliced.S == N * plain.S and sliced.va_offset(1) == sliced.S
+    a = AllocatorModel(N, 2, 8192, H, D, 2, 2 * MiB, 10 ** 6); a.alloc_reqid(); a.step([1, 0])
+    b = AllocatorModel(N, 2, 8192, H, D, 2, 2 * MiB, 10 ** 6, sliced=True); b.alloc_reqid(); b.step([1, 0])
+    assert a.map_calls == 2 * N and b.map_calls == 2
+
+
+# ---- latency hiding (Sec. 6.1) ----------------------------------------------------------------------
+
+def _decode_loop(m, lens, steps):
+    for _ in range(steps):
+        lens = [x + 1 if x else 0 for x in lens]
+        assert m.step(lens) == 0
+    return lens
+
+
+def test_lookahead_takes_decode_growth_off_the_critical_path():
+    kw = dict(N=2, B=4, L=5000, H=4, D=128, P=2, page_group_bytes=64 * KiB, pool_page_groups=4000)
+    sync = AllocatorModel(**kw)
+    over = AllocatorModel(**kw, background=True, lookahead_tokens=1)
+    lens = [100, 37, 0, 0]
+    for m in (sync, over):
+        m.alloc_reqid(); m.alloc_reqid()
+        assert m.step(lens) == 0
+    first = over.sync_map_calls
+    _decode_loop(sync, lens, 300); _decode_loop(over, lens, 300)
+    # every page-group a decode step needs was mapped by the pass after the previous step
+    assert over.sync_map_calls == first and over.background_map_calls > 0
+    # the overlapped manager is never behind and at most one token's worth of page-groups ahead
+    for r in range(4):
+        assert sync.mapped[r] <= over.mapped[r] <= sync.mapped[r] + 1
+    assert over.sync_map_calls + over.background_map_calls == over.map_calls
+    assert sync.sync_map_calls == sync.map_calls and sync.background_map_calls == 0
+
+
+def test_lookahead_skips_what_does_not_fit_and_never_fails_step():
+    m = AllocatorModel(1, 2, 1000, 1, 64, 2, 4 * KiB, pool_page_groups=4, background=True, lookahead_tokens=32)
+    a, b = m.alloc_reqid(), m.alloc_reqid()
+    assert m.step([32, 32]) == 0          # 2 rows * 2 buffers = 4 page-groups: pool empty, nothing to look ahead with
+    assert m.mapped == [1, 1] and m.pool_free == 0
+    assert m.step([33, 32]) == -1         # the demand itself still fails as before
+    assert m.mapped == [1, 1]
+
+
+def test_eager_allocation_backs_the_next_reqid():
+    m = AllocatorModel(2, 4, 4096, 2, 64, 2, 4 * KiB, pool_page_groups=400, policy="deferred", background=True,
+                       eager_page_groups=3)
+    r0 = m.alloc_reqid()
+    assert m.step([10, 0, 0, 0]) == 0
+    cand = m.next_candidate()
+    assert cand == 1 and m.mapped[cand] == 3            # topped up by the background pass
+    sync_before = m.sync_map_calls
+    r1 = m.alloc_reqid()
+    assert r1 == cand
+    lens = [10, 3 * m.tokens_per_page_group(), 0, 0]
+    assert m.step(lens) == 0
+    assert m.sync_map_calls == sync_before              # the prefill found its pages mapped
+    assert m.mapped[m.next_candidate()] == 3            # and a new candidate was prepared
+    # a finished request keeps its pages and becomes the preferred candidate when it holds more
+    assert m.free_reqid(r1) == 0 and m.next_candidate() in (r1, 2)
+    assert m.pool_free + m.nbuf * sum(m.mapped) == m.pool_total
+
+
+def test_threshold_reclaim_spares_the_candidate_and_stops_at_the_threshold():
+    m = AllocatorModel(1, 4, 4096, 1, 64, 2, 4 * KiB, pool_page_groups=40, policy="deferred", background=True,
+                       reclaim_threshold=10)
+    ids = [m.alloc_reqid() for _ in range(4)]
+    t = m.tokens_per_page_group()
+    assert m.step([5 * t, 4 * t, 4 * t, 4 * t]) == 0     # 17 rows * 2 = 34 page-groups, 6 free
+    assert m.pool_free == 6
+    for r in (0, 1, 2):
+        m.free_reqid(r)
+    assert m.mapped == [5, 4, 4, 4]                      # deferred: nothing unmapped yet
+    assert m.step([0, 0, 0, 4 * t]) == 0
+    # candidate = id 0 (most pages) is spared; id 1 gives back from the top until 10 are free
+    assert m.mapped == [5, 2, 4, 4] and m.pool_free == 10
+    assert m.unmap_calls == 4
+
+
+def test_background_conservation_on_a_random_trace():
+    rng = np.random.default_rng(77)
+    m = AllocatorModel(3, 8, 3000, 2, 64, 2, 8 * KiB, pool_page_groups=900, policy="deferred", background=True,
+                       lookahead_tokens=1, eager_page_groups=2, reclaim_threshold=120)
+    lens = [0] * 8
+    for _ in range(600):
+        op = rng.integers(0, 10)
+        if op == 0:
+            r = m.alloc_reqid()
+            if r >= 0:
+                lens[r] = int(rng.integers(1, 1500))
+        elif op == 1:
+            act = [r for r in range(8) if m.active[r]]
+            if act:
+                r = int(rng.choice(act)); m.free_reqid(r); lens[r] = 0
+        else:
+            trial = [min(x + 1, 3000) if x else 0 for x in lens]
+            if m.step(trial) == 0:
+                lens = trial
+                for r in range(8):
+                    if m.active[r]:
+                        assert m.mapped[r] >= m.need(lens[r])
+        assert m.pool_free >= 0 and m.pool_free + m.nbuf * sum(m.mapped) == m.pool_total
