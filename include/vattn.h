@@ -40,6 +40,28 @@ typedef struct vattn_ctx vattn_ctx; /* opaque */
 #define VATTN_POLICY_SYNC_UNMAP 0u /* free_reqid unmaps everything at once                      */
 #define VATTN_POLICY_DEFERRED 1u   /* pages stay mapped; alloc_reqid prefers the best-backed id;
                                       step() reclaims from inactive ids only when the pool is short */
+#define VATTN_POLICY_MASK 0xFu
+
+/* Option bits, or-ed into vattn_config.flags next to the policy. */
+#define VATTN_FLAG_BACKGROUND 0x10u     /* Sec. 6.1: after every successful step() a helper thread runs a
+                                           background pass while the caller launches the iteration's kernels:
+                                           (1) look-ahead - map what lookahead_tokens more tokens per active
+                                           request will need (Sec. 6.1.1); under DEFERRED also (2) give pages
+                                           of inactive ids back while fewer than reclaim_threshold_page_groups
+                                           are free, sparing the id alloc_reqid would return next, and
+                                           (3) top that id up to eager_page_groups (Sec. 6.1.2).  The pass is
+                                           best effort (what does not fit the free pool is skipped) and is
+                                           joined by the next call that reads or changes the bookkeeping, so
+                                           the state at every call boundary is deterministic.  With this flag
+                                           free_reqid() may only be called once the request's last kernel has
+                                           finished: its pages can be unmapped at any time afterwards.      */
+#define VATTN_FLAG_STATIC_BACKING 0x20u /* baseline for comparisons: every buffer is fully allocated with
+                                           hipMalloc at init (B*S bytes each) and map/unmap only do the
+                                           bookkeeping - the static reservation of pre-paging systems       */
+#define VATTN_FLAG_TENSOR_SLICING 0x40u /* Discussion section, "tensor slicing": ONE K and ONE V buffer of
+                                           shape [B, L, N, H, D]; a page-group holds the tokens of all N
+                                           layers, layer n is the slice [:, :, n]; 2 handles per page-group
+                                           row instead of 2N, S = L*N*H*D*P                                  */
 
 /* Arguments of init() in Table 4: N, B, L, H, D, P, page-group size (plus what a C library needs). */
 typedef struct {
@@ -55,14 +77,20 @@ typedef struct {
     int64_t phys_budget_bytes; /* size of the physical page-group pool created at init, summed
                                   over all 2N buffers; rounded down to whole page-groups          */
     int32_t device;            /* HIP device ordinal                                              */
-    uint32_t flags;            /* VATTN_POLICY_*                                                  */
+    uint32_t flags;            /* VATTN_POLICY_* | VATTN_FLAG_*                                   */
+    int32_t lookahead_tokens;  /* BACKGROUND: tokens of growth mapped ahead of need (1 = next decode
+                                  iteration); 0 = none                                            */
+    int32_t eager_page_groups; /* BACKGROUND + DEFERRED: page-groups kept mapped under the reqId that
+                                  will be handed out next; 0 = none                               */
+    int64_t reclaim_threshold_page_groups; /* BACKGROUND + DEFERRED: free-pool level below which
+                                  inactive ids give their page-groups back; 0 = never             */
 } vattn_config;
 
 /* ---- memory management: Table 4 and Algorithm 1 of the paper -------------------------------- */
 
 /* init (Table 4; Sec. 5.3.1): reserves 2N virtual buffers of B*S bytes each, S = L*H*D*P rounded
- * up to the page-group size (Sec. 5.1.3), and creates the physical page-group pool WITHOUT mapping
- * any of it.  *out receives the context.  Fails if the device lacks virtual-memory support, the
+ * up to the page-group size (Sec. 5.1.3) - with TENSOR_SLICING, 2 buffers and S = L*N*H*D*P - and
+ * creates the physical page-group pool WITHOUT mapping any of it.  *out receives the context.  Fails if the device lacks virtual-memory support, the
  * configuration is invalid, or the pool cannot be created. */
 int vattn_init(const vattn_config* cfg /*host*/, vattn_ctx** out /*host*/);
 
@@ -90,9 +118,10 @@ int vattn_free_reqid(vattn_ctx* ctx, int reqid);
 int vattn_step(vattn_ctx* ctx, const int64_t* seq_lens /*host*/, int count);
 
 /* Request-level indexing (Sec. 5.2.3): device address of reqId's sub-tensor in layer `layer`,
- * which = 0 for K, 1 for V: buffer base + reqId*S.  Layout inside: [L, H, D], token-major.
- * NULL on an invalid argument.  Only the first mapped_page_groups*page_group_bytes bytes may be
- * touched. */
+ * which = 0 for K, 1 for V: buffer base + reqId*S.  Layout inside: [L, H, D], token-major; with
+ * TENSOR_SLICING [L, N, H, D] and the returned address is that of (token 0, layer), so consecutive
+ * tokens of the layer are N*H*D*P bytes apart.  NULL on an invalid argument.  Only the first
+ * mapped_page_groups*page_group_bytes bytes of the sub-tensor may be touched. */
 void* vattn_kv_ptr(vattn_ctx* ctx, int layer, int which, int reqid);
 
 /* Introspection for tests: active flag, page-groups mapped per sub-tensor (identical in all 2N
@@ -106,6 +135,26 @@ int vattn_stats(vattn_ctx* ctx, int64_t* page_group_bytes, int64_t* S_bytes, int
 /* Cumulative number of (buffer, page-group) map and unmap operations, and the wall time in
  * microseconds the library spent inside hipMemMap+hipMemSetAccess and hipMemUnmap. */
 int vattn_counters(vattn_ctx* ctx, int64_t* map_calls, int64_t* unmap_calls, double* map_us, double* unmap_us);
+
+/* Where the mapping work happened (Sec. 6.1, the ablation of Sec. 7.5): map operations done inside
+ * step() on the caller's thread vs by background passes, and cumulative microseconds of step()
+ * calls, of background passes, and of the caller waiting for a pass to finish.  Any pointer may be
+ * NULL. */
+int vattn_step_counters(vattn_ctx* ctx, int64_t* sync_map_calls, int64_t* background_map_calls, double* step_us,
+                        double* background_us, double* wait_us);
+
+/* Waits for a running background pass (no-op without VATTN_FLAG_BACKGROUND).  Other calls do this by
+ * themselves; exposed so that measurements can separate the pass from what follows. */
+int vattn_sync(vattn_ctx* ctx);
+
+/* Per-call latency of the HIP virtual-memory API at one page-group size (the analogue of Table 3 of
+ * the paper): creates, maps, touches and tears down `count` page-groups of `bytes` each on `device`
+ * and writes average microseconds per call to out_us[9] (host):
+ *   0 hipMemAddressReserve   1 hipMemCreate   2 hipMemMap   3 hipMemSetAccess (one page-group per call)
+ *   4 hipMemSetAccess, one call over all page-groups (total)   5 hipMemUnmap   6 hipMemRelease
+ *   7 hipMemAddressFree      8 a kernel writing every mapped byte once (total).
+ * Needs no context.  `bytes` must be a multiple of the allocation granularity. */
+int vattn_vmm_microbench(int device, int64_t bytes, int count, double* out_us /*host*/);
 
 /* ---- the attention path (Eq. 2 of the paper, evaluated per request) -------------------------- */
 

@@ -3,6 +3,7 @@
 The package is a thin binding over libvattn.so (HIP kernels + C ABI, sources in csrc/).  Importing it
 requires the built library; see build.py.
 """
-from .binding import (EXPORTED, LIB_PATH, POLICY_DEFERRED, POLICY_SYNC_UNMAP, Vattn, VattnError, last_error, lib)
+from .binding import (EXPORTED, FLAG_BACKGROUND, FLAG_STATIC_BACKING, FLAG_TENSOR_SLICING, LIB_PATH, POLICY_DEFERRED,
+                      POLICY_SYNC_UNMAP, Vattn, VattnError, last_error, lib, vmm_microbench)
 
-__all__ = ["EXPORTED", "LIB_PATH", "POLICY_DEFERRED", "POLICY_SYNC_UNMAP", "Vattn", "VattnError", "last_error", "lib"]
+__all__ = ["EXPORTED", "FLAG_BACKGROUND", "FLAG_STATIC_BACKING", "FLAG_TENSOR_SLICING", "vmm_microbench", "LIB_PATH", "POLICY_DEFERRED", "POLICY_SYNC_UNMAP", "Vattn", "VattnError", "last_error", "lib"]

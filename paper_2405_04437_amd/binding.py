@@ -17,6 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libvattn.so")
 
 POLICY_SYNC_UNMAP = 0
 POLICY_DEFERRED = 1
+FLAG_BACKGROUND = 0x10
+FLAG_STATIC_BACKING = 0x20
+FLAG_TENSOR_SLICING = 0x40
 
 
 class VattnError(RuntimeError):
@@ -27,12 +30,14 @@ class _Config(ctypes.Structure):
     _fields_ = [("num_layers", ctypes.c_int32), ("max_batch", ctypes.c_int32), ("max_ctx", ctypes.c_int64),
                 ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("elem_bytes", ctypes.c_int32), ("page_group_bytes", ctypes.c_int64),
-                ("phys_budget_bytes", ctypes.c_int64), ("device", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("phys_budget_bytes", ctypes.c_int64), ("device", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("lookahead_tokens", ctypes.c_int32), ("eager_page_groups", ctypes.c_int32),
+                ("reclaim_threshold_page_groups", ctypes.c_int64)]
 
 
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2405_04437_amd.build` "
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2405_04437_amd/build.py` "
                           "(or __graft_entry__.build()); there is no CPU fallback")
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32p, i64p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
@@ -59,9 +64,13 @@ def _load() -> ctypes.CDLL:
     lib.vattn_set_decode_chunk.argtypes = [vp, ctypes.c_int]
     lib.vattn_set_decode_tuning.argtypes = [vp, ctypes.c_int]
     lib.vattn_set_prefill_wide.argtypes = [vp, ctypes.c_int]
+    lib.vattn_step_counters.argtypes = [vp, i64p, i64p, dp, dp, dp]
+    lib.vattn_sync.argtypes = [vp]
+    lib.vattn_vmm_microbench.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, dp]
     for name in ("vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_query",
                  "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill", "vattn_attn_decode",
-                 "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide"):
+                 "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide",
+                 "vattn_step_counters", "vattn_sync", "vattn_vmm_microbench"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -71,7 +80,8 @@ lib = _load()
 EXPORTED = ["vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_kv_ptr",
             "vattn_query", "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill",
             "vattn_decode_workspace_bytes", "vattn_attn_decode", "vattn_set_timing", "vattn_kernel_time",
-            "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide", "vattn_last_error"]
+            "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide", "vattn_step_counters",
+            "vattn_sync", "vattn_vmm_microbench", "vattn_last_error"]
 
 
 def last_error() -> str:
@@ -98,9 +108,11 @@ class Vattn:
 
     def __init__(self, num_layers: int, max_batch: int, max_ctx: int, num_q_heads: int, num_kv_heads: int,
                  head_dim: int, phys_budget_bytes: int, page_group_bytes: int = 0, elem_bytes: int = 2,
-                 device: int = 0, policy: int = POLICY_SYNC_UNMAP) -> None:
+                 device: int = 0, policy: int = POLICY_SYNC_UNMAP, flags: int = 0, lookahead_tokens: int = 0,
+                 eager_page_groups: int = 0, reclaim_threshold_page_groups: int = 0) -> None:
         cfg = _Config(num_layers, max_batch, max_ctx, num_q_heads, num_kv_heads, head_dim, elem_bytes,
-                      page_group_bytes, phys_budget_bytes, device, policy)
+                      page_group_bytes, phys_budget_bytes, device, policy | flags, lookahead_tokens,
+                      eager_page_groups, reclaim_threshold_page_groups)
         h = ctypes.c_void_p()
         if lib.vattn_init(ctypes.byref(cfg), ctypes.byref(h)) != 0:
             raise VattnError("vattn_init: " + last_error())
@@ -150,6 +162,16 @@ class Vattn:
         lib.vattn_counters(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d))
         return a.value, b.value, c.value, d.value
 
+    def step_counters(self) -> Tuple[int, int, float, float, float]:
+        """(map calls inside step(), map calls by background passes, us in step(), us in passes, us waiting)."""
+        a, b = ctypes.c_int64(), ctypes.c_int64()
+        c, d, e = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+        lib.vattn_step_counters(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d), ctypes.byref(e))
+        return a.value, b.value, c.value, d.value, e.value
+
+    def sync(self) -> int:
+        return lib.vattn_sync(self._h)
+
     # ---- attention path --------------------------------------------------------------------
     def append_kv(self, layer: int, stream: int, k_new, v_new, reqids, cu_q, kv_len_before) -> int:
         r, rp = _i32(reqids)
@@ -192,3 +214,11 @@ class Vattn:
 
     def set_decode_tuning(self, segments_per_slot: int) -> int:
         return lib.vattn_set_decode_tuning(self._h, segments_per_slot)
+
+
+def vmm_microbench(page_group_bytes: int, count: int, device: int = 0):
+    """Average microseconds per HIP virtual-memory call at one page-group size (see vattn.h)."""
+    out = (ctypes.c_double * 9)()
+    if lib.vattn_vmm_microbench(device, page_group_bytes, count, out) != 0:
+        raise VattnError("vattn_vmm_microbench: " + last_error())
+    return list(out)

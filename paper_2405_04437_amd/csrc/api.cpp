@@ -26,7 +26,7 @@ bool check_request(vattn_ctx* ctx, int reqid, int64_t kv_len, const char* fn) {
         set_error(std::string(fn) + ": reqId " + std::to_string(reqid) + " out of range or not active");
         return false;
     }
-    if (kv_len < 0 || kv_len > ctx->cfg.max_ctx || kv_len * ctx->mem.T() > ctx->mem.mapped(reqid) * ctx->mem.G()) {
+    if (kv_len < 0 || kv_len > ctx->cfg.max_ctx || kv_len * ctx->mem.token_stride() > ctx->mem.mapped_committed(reqid) * ctx->mem.G()) {
         set_error(std::string(fn) + ": context length " + std::to_string(kv_len) + " of reqId " + std::to_string(reqid) +
                   " exceeds what step() has mapped");
         return false;
@@ -70,7 +70,8 @@ int vattn_init(const vattn_config* cfg, vattn_ctx** out) {
     vattn_ctx* ctx = new (std::nothrow) vattn_ctx();
     if (!ctx) { set_error("init: out of host memory"); return -1; }
     ctx->cfg = *cfg;
-    if (!ctx->mem.init(*cfg)) { delete ctx; return -1; }
+    const VmmOps& ops = (cfg->flags & VATTN_FLAG_STATIC_BACKING) ? hip_static_ops() : hip_vmm_ops();
+    if (!ctx->mem.init(*cfg, ops)) { delete ctx; return -1; }
     if (!hip_ok(hipDeviceGetAttribute(&ctx->num_cus, hipDeviceAttributeMultiprocessorCount, cfg->device), "hipDeviceGetAttribute") || ctx->num_cus <= 0) { delete ctx; return -1; }
     *out = ctx;
     return 0;
@@ -112,11 +113,34 @@ int vattn_stats(vattn_ctx* ctx, int64_t* page_group_bytes, int64_t* S_bytes, int
 
 int vattn_counters(vattn_ctx* ctx, int64_t* map_calls, int64_t* unmap_calls, double* map_us, double* unmap_us) {
     if (!ctx) { set_error("counters: null context"); return -1; }
-    if (map_calls) *map_calls = ctx->mem.map_calls;
-    if (unmap_calls) *unmap_calls = ctx->mem.unmap_calls;
-    if (map_us) *map_us = ctx->mem.map_us;
-    if (unmap_us) *unmap_us = ctx->mem.unmap_us;
+    const KvMemory::Counters c = ctx->mem.counters();
+    if (map_calls) *map_calls = c.map_calls;
+    if (unmap_calls) *unmap_calls = c.unmap_calls;
+    if (map_us) *map_us = c.map_us;
+    if (unmap_us) *unmap_us = c.unmap_us;
     return 0;
+}
+
+int vattn_step_counters(vattn_ctx* ctx, int64_t* sync_map_calls, int64_t* background_map_calls, double* step_us,
+                        double* background_us, double* wait_us) {
+    if (!ctx) { set_error("step_counters: null context"); return -1; }
+    const KvMemory::Counters c = ctx->mem.counters();
+    if (sync_map_calls) *sync_map_calls = c.sync_map_calls;
+    if (background_map_calls) *background_map_calls = c.background_map_calls;
+    if (step_us) *step_us = c.step_us;
+    if (background_us) *background_us = c.background_us;
+    if (wait_us) *wait_us = c.wait_us;
+    return 0;
+}
+
+int vattn_sync(vattn_ctx* ctx) {
+    if (!ctx) { set_error("sync: null context"); return -1; }
+    ctx->mem.sync();
+    return 0;
+}
+
+int vattn_vmm_microbench(int device, int64_t bytes, int count, double* out_us) {
+    return vmm_microbench(device, bytes, count, out_us) ? 0 : -1;
 }
 
 int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new, const void* v_new,
@@ -134,7 +158,7 @@ int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new, 
     AppendArgs a{};
     a.k_new = k_new; a.v_new = v_new;
     a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1);
-    a.S = ctx->mem.S(); a.row_bytes = ctx->mem.T();
+    a.S = ctx->mem.S(); a.row_bytes = ctx->mem.T(); a.tok_stride = ctx->mem.token_stride();
     a.n = n; a.total_rows = cu_q[n];
     if (n <= kInlineMaxReq) {
         InlineMeta im;
@@ -210,7 +234,7 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, vo
     DecodeArgs a{};
     a.q = q; a.o = o;
     a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1); a.S = ctx->mem.S();
-    a.Hq = Hq; a.H = ctx->cfg.num_kv_heads; a.D = D;
+    a.Hq = Hq; a.H = ctx->cfg.num_kv_heads; a.D = D; a.row_stride = static_cast<int>(ctx->mem.token_stride());
     a.inline_meta = inl ? 1 : 0;
     a.reqids = reinterpret_cast<const int32_t*>(d);
     a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
@@ -287,7 +311,7 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
     PrefillArgs a{};
     a.q = q; a.o = o;
     a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1); a.S = ctx->mem.S();
-    a.Hq = Hq; a.H = H; a.D = D;
+    a.Hq = Hq; a.H = H; a.D = D; a.row_stride = static_cast<int>(ctx->mem.token_stride());
     a.reqids = reinterpret_cast<const int32_t*>(d);
     a.cu_q = reinterpret_cast<const int32_t*>(d + off_cu);
     a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);

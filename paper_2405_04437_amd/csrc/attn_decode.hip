@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
         const int mid = (lo + hi) >> 1;
         if (cu_of(mid) <= T0) lo = mid; else hi = mid;
     }
-    const int64_t row_stride = static_cast<int64_t>(a.H) * G::RB;
+    const int row_stride = a.row_stride;   // bytes between consecutive tokens of this layer
     char* klds = lds_raw + wave * G::WAVE_LDS;
     char* vlds = klds + kTile * G::KSTR;
     const int hl = hb * 16 + (l & 15);
@@ -119,24 +119,23 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
 
     const int ld_row = l / G::LPR;            // row inside one load instruction
     const int ld_col = (l % G::LPR) * 16;     // byte offset inside the row
-    const int lane_off = ld_row * static_cast<int>(row_stride) + ld_col;
+    const int lane_off = ld_row * row_stride + ld_col;
     u32x4 kreg[G::NL], vreg[G::NL];
-    // K and V of this (request, KV head) as raw buffer resources: the loads then take one 32-bit
-    // per-lane offset plus a scalar offset, so all tile/row address arithmetic runs on the scalar unit.
-    // num_records ends at the last valid row of this head: reads beyond it are suppressed by the
-    // hardware range check and return zero.
-    const int nrec = (kv_len - 1) * static_cast<int>(row_stride) + G::RB;
-    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kp), 0, nrec, kRsrcWord3);
-    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vp), 0, nrec, kRsrcWord3);
+    // K and V of one tile of this (request, KV head) as raw buffer resources: the loads take one 32-bit
+    // per-lane offset (the same for the whole kernel) plus a scalar offset per instruction, and the
+    // 64-bit address of the tile is scalar arithmetic, so sub-tensors of any size are addressable.
+    // num_records ends at the last valid row of the tile: rows past the end of the context (ragged last
+    // tile) are suppressed by the hardware range check - they return zeros and touch nothing, so no
+    // byte beyond what step() has mapped is read; their scores are masked below.
     auto issue_loads = [&](u32x4 (&kreg)[G::NL], u32x4 (&vreg)[G::NL], int t) {
-        // One per-lane offset for the whole kernel plus a scalar offset per load instruction.  Rows past
-        // the end of the context (ragged last tile) lie beyond num_records: the hardware range check
-        // returns zeros for them and touches nothing, so no byte beyond what step() has mapped is read;
-        // their scores are masked below.
-        const int sbase = (tok0 + t * kTile) * static_cast<int>(row_stride);
+        const int tok = tok0 + t * kTile;
+        const int64_t boff = static_cast<int64_t>(tok) * row_stride;
+        const int nrec = (min(kv_len - tok, kTile) - 1) * row_stride + G::RB;
+        const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kp + boff), 0, nrec, kRsrcWord3);
+        const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vp + boff), 0, nrec, kRsrcWord3);
 #pragma unroll
         for (int i = 0; i < G::NL; ++i) {
-            const int so = sbase + i * G::RPI * static_cast<int>(row_stride);
+            const int so = i * G::RPI * row_stride;
             kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, lane_off, so, kAuxNt);
             vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, lane_off, so, kAuxNt);
         }

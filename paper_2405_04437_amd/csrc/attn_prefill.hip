@@ -82,12 +82,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
     const int n_kv = q_last + off + 1;         // keys any row of this tile can see
     const int ntiles = (n_kv + kBN - 1) / kBN;
 
-    const int rs32 = a.H * G::RB;              // bytes between consecutive tokens
+    const int rs32 = a.row_stride;             // bytes between consecutive tokens of this layer
     const int64_t sub = static_cast<int64_t>(a.reqids[req]) * a.S + static_cast<int64_t>(it.kvh) * G::RB;
-    // K and V of this (request, KV head) as raw buffer resources: scalar base, one 32-bit per-lane offset.
-    const int nrec = (kv_len - 1) * rs32 + G::RB;
-    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(a.k_base + sub), 0, nrec, kRsrcWord3);
-    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(a.v_base + sub), 0, nrec, kRsrcWord3);
+    const char* kp = a.k_base + sub;
+    const char* vp = a.v_base + sub;
 
     // Q^T as B operand: lane (n = l%32, h = l/32) holds Q[row n][ks*16 + h*8 .. +8], per query block
     const int row_lo = q0 + w * WR;               // first query row of this wave
@@ -105,9 +103,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
 
     const int ld_row = tid / G::LPR;
     const int ld_col = (tid % G::LPR) * 16;
-    // Global addressing: one per-lane offset for the whole kernel + a scalar offset per load.  Rows past
-    // the end of the context lie beyond num_records; the hardware range check returns zeros for them and
-    // touches nothing, so no byte beyond what step() has mapped is read (their scores are masked).
+    // Global addressing: each tile of K and V is a raw buffer resource whose 64-bit base is scalar
+    // arithmetic (sub-tensors of any size are addressable); the loads add one per-lane offset, the same
+    // for the whole kernel, and a scalar offset per instruction.  num_records ends at the last row of
+    // the context: rows past it fail the hardware range check, return zeros and touch nothing, so no
+    // byte beyond what step() has mapped is read (their scores are masked).
     const int lane_off = ld_row * rs32 + ld_col;
     // One register set stages the next tile: it is requested right after the score multiplies of tile t
     // have been issued and written to the other LDS buffer at the end of the iteration.  The issue is
@@ -116,9 +116,15 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
     // flight across the softmax and the second contraction.
     u32x4 kregA[G::NL], vregA[G::NL];
     auto issue_loads = [&](u32x4 (&kreg)[G::NL], u32x4 (&vreg)[G::NL], int t) {
+        const int tok = t * kBN;
+        const int64_t boff = static_cast<int64_t>(tok) * rs32;
+        const int rows = min(kv_len - tok, kBN);   // <= 0 past the end: everything out of range
+        const int nrec = rows > 0 ? (rows - 1) * rs32 + G::RB : 0;
+        const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kp + boff), 0, nrec, kRsrcWord3);
+        const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vp + boff), 0, nrec, kRsrcWord3);
 #pragma unroll
         for (int i = 0; i < G::NL; ++i) {
-            const int so = (t * kBN + i * G::RPI) * rs32;   // scalar; rows past the context are out of range
+            const int so = i * G::RPI * rs32;
             kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, lane_off, so, 0);
             vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, lane_off, so, 0);
         }

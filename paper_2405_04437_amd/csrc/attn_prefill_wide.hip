@@ -84,11 +84,10 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_wide_kernel(PrefillArgs a
     // tiles both of whose half-steps can be pipelined (the step after each is still unmasked)
     const int tiles_piped = h_full >= 2 ? (h_full - 1) / 2 : 0;
 
-    const int rs32 = a.H * G::RB;
+    const int rs32 = a.row_stride;             // bytes between consecutive tokens of this layer
     const int64_t sub = static_cast<int64_t>(a.reqids[req]) * a.S + static_cast<int64_t>(it.kvh) * G::RB;
-    const int nrec = (kv_len - 1) * rs32 + G::RB;
-    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(a.k_base + sub), 0, nrec, kRsrcWord3);
-    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(a.v_base + sub), 0, nrec, kRsrcWord3);
+    const char* kp = a.k_base + sub;
+    const char* vp = a.v_base + sub;
 
     const int row_lo = q0 + w * 64;
     int my_row[2];
@@ -105,15 +104,23 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_wide_kernel(PrefillArgs a
 
     const int ld_row = tid / G::LPR;
     const int ld_col = (tid % G::LPR) * 16;
-    // Global addressing: one per-lane offset for the whole kernel + a scalar offset per load.  Rows past
-    // the end of the context lie beyond num_records; the hardware range check returns zeros for them and
-    // touches nothing, so no byte beyond what step() has mapped is read (their scores are masked).
+    // Global addressing: each tile of K and V is a raw buffer resource whose 64-bit base is scalar
+    // arithmetic (sub-tensors of any size are addressable); the loads add one per-lane offset, the same
+    // for the whole kernel, and a scalar offset per instruction.  num_records ends at the last row of
+    // the context: rows past it fail the hardware range check, return zeros and touch nothing, so no
+    // byte beyond what step() has mapped is read (their scores are masked).
     const int lane_off = ld_row * rs32 + ld_col;
     u32x4 kreg[G::NL], vreg[G::NL];
     auto issue_loads = [&](int T) {
+        const int tok = T * kTile;
+        const int64_t boff = static_cast<int64_t>(tok) * rs32;
+        const int rows = min(kv_len - tok, kTile);   // <= 0 past the end: everything out of range
+        const int nrec = rows > 0 ? (rows - 1) * rs32 + G::RB : 0;
+        const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kp + boff), 0, nrec, kRsrcWord3);
+        const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vp + boff), 0, nrec, kRsrcWord3);
 #pragma unroll
         for (int i = 0; i < G::NL; ++i) {
-            const int so = (T * kTile + i * G::RPI) * rs32;   // scalar; rows past the context are out of range
+            const int so = i * G::RPI * rs32;
             kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, lane_off, so, 0);
             vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, lane_off, so, 0);
         }

@@ -1,7 +1,8 @@
 // KV append: the new K and V rows of every request are copied to the end of its virtually
 // contiguous sub-tensor ("a single tensor copy" - Sec. 7.1 of the paper).  Pure data movement:
-// 16 bytes per lane, rows are H*D*P bytes and land at consecutive addresses, so both the reads and
-// the writes are fully coalesced.
+// 16 bytes per lane, rows are H*D*P bytes and land at consecutive addresses (tok_stride = H*D*P; with
+// the all-layers-in-one-buffer layout consecutive tokens of a layer are N*H*D*P apart and each row is
+// still one contiguous piece), so both the reads and the writes are fully coalesced.
 #include "vattn_internal.h"
 
 namespace vattn {
@@ -31,7 +32,7 @@ __global__ __launch_bounds__(256) void append_kv_kernel(AppendArgs a, InlineMeta
             if (cu_of(mid) <= row) lo = mid; else hi = mid;
         }
         const int64_t tok = static_cast<int64_t>(before_of(lo)) + (row - cu_of(lo));
-        char* dst = dst_base + static_cast<int64_t>(reqid_of(lo)) * a.S + tok * a.row_bytes + piece * 16;
+        char* dst = dst_base + static_cast<int64_t>(reqid_of(lo)) * a.S + tok * a.tok_stride + piece * 16;
         *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(src + i * 16);
     }
 }

@@ -1,14 +1,14 @@
-// KV-cache memory manager on the HIP virtual-memory API.
+// KV-cache memory manager (bookkeeping; see kv_memory.h).
 //
-// Design (Sec. 5 of the paper, re-expressed for HIP): virtual address space is reserved once for
-// the largest batch and context (hipMemAddressReserve), physical page-groups are created up front
-// (hipMemCreate) but mapped (hipMemMap + hipMemSetAccess) only when step() sees that a request's
-// context has outgrown what is backed.  One physical handle per page-group: HIP rejects mapping a
-// handle at a non-zero offset, so a page-group is the unit of both creation and mapping.
-#include <chrono>
-#include <thread>
+// Design (Sec. 5 of the paper, re-expressed for HIP): virtual address space is reserved once for the
+// largest batch and context, physical page-groups are created up front but mapped only when step()
+// sees that a request's context has outgrown what is backed.  One physical handle per page-group: HIP
+// rejects mapping a handle at a non-zero offset, so a page-group is the unit of both creation and
+// mapping.  With the background option (Sec. 6.1) a helper thread maps the next iteration's growth,
+// prepares the next reqId and reclaims deferred pages while the caller runs the current iteration.
+#include "kv_memory.h"
 
-#include "vattn_internal.h"
+#include <chrono>
 
 namespace vattn {
 
@@ -22,14 +22,58 @@ double now_us() {
 void set_error(const std::string& msg) { g_error = msg; }
 const std::string& last_error_string() { return g_error; }
 
-bool hip_ok(hipError_t e, const char* what) {
-    if (e == hipSuccess) return true;
-    set_error(std::string(what) + ": " + hipGetErrorString(e));
-    (void)hipGetLastError();  // clear the sticky error so later calls are not blamed for it
-    return false;
+// ---------------------------------------------------------------------------------------------
+
+Worker::~Worker() {
+    if (!thread_.joinable()) return;
+    {
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_.wait(lk, [&] { return !busy_; });
+        stop_ = true;
+    }
+    cv_.notify_all();
+    thread_.join();
 }
 
-bool KvMemory::init(const vattn_config& c) {
+void Worker::start(std::function<void()> on_start) {
+    thread_ = std::thread([this, on_start] { loop(on_start); });
+}
+
+void Worker::loop(std::function<void()> on_start) {
+    if (on_start) on_start();
+    std::unique_lock<std::mutex> lk(mu_);
+    for (;;) {
+        cv_.wait(lk, [&] { return stop_ || busy_; });
+        if (stop_) return;
+        std::function<void()> t = std::move(task_);
+        task_ = nullptr;
+        lk.unlock();
+        t();
+        lk.lock();
+        busy_ = false;
+        cv_.notify_all();
+    }
+}
+
+void Worker::submit(std::function<void()> task) {
+    {
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_.wait(lk, [&] { return !busy_; });
+        task_ = std::move(task);
+        busy_ = true;
+    }
+    cv_.notify_all();
+}
+
+void Worker::wait() {
+    std::unique_lock<std::mutex> lk(mu_);
+    cv_.wait(lk, [&] { return !busy_; });
+}
+
+// ---------------------------------------------------------------------------------------------
+
+bool KvMemory::init(const vattn_config& c, const VmmOps& ops) {
+    ops_ = ops;
     if (c.num_layers <= 0 || c.max_batch <= 0 || c.max_ctx <= 0 || c.num_kv_heads <= 0 ||
         c.num_q_heads <= 0 || c.num_q_heads % c.num_kv_heads != 0) {
         set_error("init: N, B, L, H must be positive and Hq a multiple of H");
@@ -37,19 +81,20 @@ bool KvMemory::init(const vattn_config& c) {
     }
     if (c.head_dim != 64 && c.head_dim != 128) { set_error("init: head_dim must be 64 or 128"); return false; }
     if (c.elem_bytes != 2) { set_error("init: only 2-byte (bf16) elements are supported"); return false; }
-    if (c.flags != VATTN_POLICY_SYNC_UNMAP && c.flags != VATTN_POLICY_DEFERRED) { set_error("init: unknown policy flag"); return false; }
+    const uint32_t known = VATTN_POLICY_MASK | VATTN_FLAG_BACKGROUND | VATTN_FLAG_STATIC_BACKING | VATTN_FLAG_TENSOR_SLICING;
+    policy_ = c.flags & VATTN_POLICY_MASK;
+    if ((c.flags & ~known) != 0 || (policy_ != VATTN_POLICY_SYNC_UNMAP && policy_ != VATTN_POLICY_DEFERRED)) {
+        set_error("init: unknown policy or flag bits");
+        return false;
+    }
+    if (c.lookahead_tokens < 0 || c.eager_page_groups < 0 || c.reclaim_threshold_page_groups < 0) {
+        set_error("init: negative look-ahead, eager or threshold value");
+        return false;
+    }
     device_ = c.device;
-    if (!hip_ok(hipSetDevice(device_), "hipSetDevice")) return false;
-    int vmm = 0;
-    if (!hip_ok(hipDeviceGetAttribute(&vmm, hipDeviceAttributeVirtualMemoryManagementSupported, device_), "hipDeviceGetAttribute")) return false;
-    if (!vmm) { set_error("init: device does not support virtual memory management"); return false; }
-
-    hipMemAllocationProp prop{};
-    prop.type = hipMemAllocationTypePinned;
-    prop.location.type = hipMemLocationTypeDevice;
-    prop.location.id = device_;
+    if (!ops_.bind_thread(device_)) return false;
     size_t gran = 0;
-    if (!hip_ok(hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityMinimum), "hipMemGetAllocationGranularity")) return false;
+    if (!ops_.granularity(device_, &gran)) return false;
     if (gran == 0) { set_error("init: zero allocation granularity"); return false; }
     int64_t G = c.page_group_bytes == 0 ? (int64_t{2} << 20) : c.page_group_bytes;
     if (c.page_group_bytes == 0) G = (G + static_cast<int64_t>(gran) - 1) / static_cast<int64_t>(gran) * static_cast<int64_t>(gran);
@@ -57,77 +102,101 @@ bool KvMemory::init(const vattn_config& c) {
         set_error("init: page_group_bytes must be a positive multiple of the allocation granularity (" + std::to_string(gran) + ")");
         return false;
     }
-    N_ = c.num_layers; B_ = c.max_batch; L_ = c.max_ctx; policy_ = c.flags; G_ = G;
+    N_ = c.num_layers; B_ = c.max_batch; L_ = c.max_ctx; G_ = G;
+    sliced_ = (c.flags & VATTN_FLAG_TENSOR_SLICING) != 0;
+    background_ = (c.flags & VATTN_FLAG_BACKGROUND) != 0;
+    lookahead_ = c.lookahead_tokens; eager_ = c.eager_page_groups; reclaim_threshold_ = c.reclaim_threshold_page_groups;
+    nbuf_ = sliced_ ? 2 : 2 * N_;
     T_ = static_cast<int64_t>(c.num_kv_heads) * c.head_dim * c.elem_bytes;
-    S_ = (L_ * T_ + G_ - 1) / G_ * G_;
-    if (S_ >= (int64_t{1} << 31)) { set_error("init: one request's sub-tensor (L*H*D*P) must stay below 2 GiB (32-bit buffer offsets in the kernels)"); return false; }
+    Tbuf_ = sliced_ ? T_ * N_ : T_;
+    if (L_ > (int64_t{1} << 40) / Tbuf_) { set_error("init: L*H*D*P does not fit the address arithmetic"); return false; }
+    S_ = (L_ * Tbuf_ + G_ - 1) / G_ * G_;
     pool_total_ = c.phys_budget_bytes / G_;
     if (pool_total_ < 0) { set_error("init: negative physical budget"); return false; }
 
-    access_.location.type = hipMemLocationTypeDevice;
-    access_.location.id = device_;
-    access_.flags = hipMemAccessFlagsProtReadWrite;
-
     const size_t buf_bytes = static_cast<size_t>(B_) * static_cast<size_t>(S_);
-    base_.assign(static_cast<size_t>(2) * N_, nullptr);
+    base_.assign(static_cast<size_t>(nbuf_), nullptr);
     for (size_t b = 0; b < base_.size(); ++b) {
         void* p = nullptr;
-        if (!hip_ok(hipMemAddressReserve(&p, buf_bytes, static_cast<size_t>(G_), nullptr, 0), "hipMemAddressReserve")) return false;
+        if (!ops_.reserve(&p, buf_bytes, static_cast<size_t>(G_))) return false;
         base_[b] = static_cast<char*>(p);
     }
     free_handles_.reserve(static_cast<size_t>(pool_total_));
     for (int64_t i = 0; i < pool_total_; ++i) {
-        hipMemGenericAllocationHandle_t h;
-        if (!hip_ok(hipMemCreate(&h, static_cast<size_t>(G_), &prop, 0), "hipMemCreate (physical pool)")) return false;
+        uint64_t h = 0;
+        if (!ops_.create(&h, static_cast<size_t>(G_), device_)) return false;
         free_handles_.push_back(h);
     }
     held_.assign(static_cast<size_t>(B_), {});
     active_.assign(static_cast<size_t>(B_), 0);
     mapped_.assign(static_cast<size_t>(B_), 0);
+    committed_.assign(static_cast<size_t>(B_), 0);
+    if (background_) {
+        const VmmOps o = ops_;
+        const int dev = device_;
+        worker_.start([o, dev] { (void)o.bind_thread(dev); });
+    }
     return true;
 }
 
 KvMemory::~KvMemory() {
     if (base_.empty()) return;
-    (void)hipSetDevice(device_);
-    (void)hipDeviceSynchronize();
+    sync();
+    (void)ops_.bind_thread(device_);
+    (void)ops_.device_sync();
     for (int r = 0; r < B_; ++r) unmap_rows(r, 0);
-    for (auto h : free_handles_) (void)hipMemRelease(h);
+    for (auto h : free_handles_) (void)ops_.release(h);
     const size_t buf_bytes = static_cast<size_t>(B_) * static_cast<size_t>(S_);
-    for (char* p : base_) if (p) (void)hipMemAddressFree(p, buf_bytes);
+    for (char* p : base_) if (p) (void)ops_.va_free(p, buf_bytes);
 }
 
-int KvMemory::alloc_reqid() {
+void KvMemory::sync() {
+    if (!pass_pending_) return;
+    const double t0 = now_us();
+    worker_.wait();
+    c_.wait_us += now_us() - t0;
+    pass_pending_ = false;
+    committed_ = mapped_;
+}
+
+int KvMemory::next_candidate() const {
     int best = -1;
     for (int r = 0; r < B_; ++r) {
         if (active_[r]) continue;
         if (best < 0) { best = r; if (policy_ == VATTN_POLICY_SYNC_UNMAP) break; continue; }
         if (mapped_[r] > mapped_[best]) best = r;  // most pages still mapped; ties keep the lowest id
     }
+    return best;
+}
+
+int KvMemory::alloc_reqid() {
+    sync();
+    const int best = next_candidate();
     if (best < 0) { set_error("alloc_reqid: all reqIds are in use"); return -1; }
     active_[best] = 1;
     return best;
 }
 
 int KvMemory::free_reqid(int r) {
+    sync();
     if (!valid_reqid(r) || !active_[r]) { set_error("free_reqid: reqId out of range or not active"); return -1; }
     active_[r] = 0;
-    if (policy_ == VATTN_POLICY_SYNC_UNMAP) unmap_rows(r, 0);
+    if (policy_ == VATTN_POLICY_SYNC_UNMAP) { unmap_rows(r, 0); committed_[r] = 0; }
     return 0;
 }
 
-bool KvMemory::map_rows(int r, int64_t from, int64_t to) {
+bool KvMemory::map_rows(int r, int64_t from, int64_t to, bool background) {
     const size_t nb = base_.size();
     auto& held = held_[r];
     const double t0 = now_us();
     for (int64_t k = from; k < to; ++k) {
         for (size_t b = 0; b < nb; ++b) {
-            hipMemGenericAllocationHandle_t h = free_handles_.back();
+            const uint64_t h = free_handles_.back();
             char* va = base_[b] + static_cast<int64_t>(r) * S_ + k * G_;
-            if (!hip_ok(hipMemMap(va, static_cast<size_t>(G_), 0, h, 0), "hipMemMap")) {
+            if (!ops_.map(va, static_cast<size_t>(G_), h)) {
                 // undo the partial row and everything mapped by this call
                 for (size_t u = 0; u < b; ++u) {
-                    (void)hipMemUnmap(base_[u] + static_cast<int64_t>(r) * S_ + k * G_, static_cast<size_t>(G_));
+                    (void)ops_.unmap(base_[u] + static_cast<int64_t>(r) * S_ + k * G_, static_cast<size_t>(G_));
                     free_handles_.push_back(held.back()); held.pop_back();
                 }
                 mapped_[r] = k; unmap_rows(r, from);
@@ -135,19 +204,20 @@ bool KvMemory::map_rows(int r, int64_t from, int64_t to) {
             }
             free_handles_.pop_back();
             held.push_back(h);
-            ++map_calls;
+            ++c_.map_calls;
+            ++(background ? c_.background_map_calls : c_.sync_map_calls);
         }
         mapped_[r] = k + 1;
     }
     // One access call per buffer covers the whole newly mapped, contiguous range.
     for (size_t b = 0; b < nb; ++b) {
         char* va = base_[b] + static_cast<int64_t>(r) * S_ + from * G_;
-        if (!hip_ok(hipMemSetAccess(va, static_cast<size_t>((to - from) * G_), &access_, 1), "hipMemSetAccess")) {
+        if (!ops_.set_access(va, static_cast<size_t>((to - from) * G_), device_)) {
             unmap_rows(r, from);
             return false;
         }
     }
-    map_us += now_us() - t0;
+    c_.map_us += now_us() - t0;
     return true;
 }
 
@@ -157,17 +227,19 @@ void KvMemory::unmap_rows(int r, int64_t keep) {
     const double t0 = now_us();
     for (int64_t k = mapped_[r] - 1; k >= keep; --k) {
         for (size_t b = nb; b-- > 0;) {
-            (void)hipMemUnmap(base_[b] + static_cast<int64_t>(r) * S_ + k * G_, static_cast<size_t>(G_));
+            (void)ops_.unmap(base_[b] + static_cast<int64_t>(r) * S_ + k * G_, static_cast<size_t>(G_));
             free_handles_.push_back(held.back());
             held.pop_back();
-            ++unmap_calls;
+            ++c_.unmap_calls;
         }
     }
     if (mapped_[r] > keep) mapped_[r] = keep;
-    unmap_us += now_us() - t0;
+    c_.unmap_us += now_us() - t0;
 }
 
 int KvMemory::step(const int64_t* seq_lens, int count) {
+    const double t_begin = now_us();
+    sync();
     if (!seq_lens || count != B_) { set_error("step: seq_lens must have exactly B entries"); return -1; }
     std::vector<int64_t> want(static_cast<size_t>(B_), 0);
     int64_t demand_rows = 0, reclaimable_rows = 0;
@@ -179,105 +251,67 @@ int KvMemory::step(const int64_t* seq_lens, int count) {
             reclaimable_rows += mapped_[r];
             continue;
         }
-        const int64_t need = (n * T_ + G_ - 1) / G_;  // (s + t - 1) / t
-        want[r] = need > mapped_[r] ? need : mapped_[r];
+        const int64_t nd = need(n);
+        want[r] = nd > mapped_[r] ? nd : mapped_[r];
         demand_rows += want[r] - mapped_[r];
     }
-    const int64_t per_row = static_cast<int64_t>(base_.size());
+    const int64_t per_row = nbuf_;
     const int64_t demand = demand_rows * per_row;
-    if (demand > pool_free() + reclaimable_rows * per_row) {
-        set_error("step: physical pool exhausted (demand " + std::to_string(demand) + " page-groups, free " + std::to_string(pool_free()) + ")");
+    if (demand > free_now() + reclaimable_rows * per_row) {
+        set_error("step: physical pool exhausted (demand " + std::to_string(demand) + " page-groups, free " + std::to_string(free_now()) + ")");
         return -1;
     }
-    if (demand > pool_free()) {  // deferred policy: take pages back from inactive ids, lowest id first
-        for (int r = 0; r < B_ && pool_free() < demand; ++r) {
+    if (demand > free_now()) {  // deferred policy: take pages back from inactive ids, lowest id first
+        for (int r = 0; r < B_ && free_now() < demand; ++r) {
             if (active_[r]) continue;
-            while (mapped_[r] > 0 && pool_free() < demand) unmap_rows(r, mapped_[r] - 1);
+            while (mapped_[r] > 0 && free_now() < demand) unmap_rows(r, mapped_[r] - 1);
         }
     }
+    int rc = 0;
     for (int r = 0; r < B_; ++r) {
         if (!active_[r] || want[r] <= mapped_[r]) continue;
-        if (!map_rows(r, mapped_[r], want[r])) return -1;
+        if (!map_rows(r, mapped_[r], want[r], false)) { rc = -1; break; }
     }
-    return 0;
-}
-
-// ---------------------------------------------------------------------------------------------
-
-MetaRing::~MetaRing() {
-    for (int i = 0; i < kSlots; ++i) if (ev_[i]) (void)hipEventDestroy(ev_[i]);
-    if (host_) (void)hipHostFree(host_);
-    if (dev_) (void)hipFree(dev_);
-}
-
-bool MetaRing::grow(size_t bytes) {
-    if (!hip_ok(hipDeviceSynchronize(), "hipDeviceSynchronize")) return false;
-    if (host_) { (void)hipHostFree(host_); host_ = nullptr; }
-    if (dev_) { (void)hipFree(dev_); dev_ = nullptr; }
-    size_t sz = 64 * 1024;
-    while (sz < bytes) sz *= 2;
-    if (!hip_ok(hipHostMalloc(reinterpret_cast<void**>(&host_), sz * kSlots, hipHostMallocDefault), "hipHostMalloc")) return false;
-    if (!hip_ok(hipMalloc(reinterpret_cast<void**>(&dev_), sz * kSlots), "hipMalloc (index staging)")) return false;
-    slot_bytes_ = sz;
-    for (int i = 0; i < kSlots; ++i) {
-        pending_[i] = false;
-        if (!ev_[i] && !hip_ok(hipEventCreateWithFlags(&ev_[i], hipEventDisableTiming), "hipEventCreate")) return false;
+    committed_ = mapped_;
+    if (rc == 0 && background_) {
+        std::vector<int64_t> lens(seq_lens, seq_lens + B_);
+        pass_pending_ = true;
+        worker_.submit([this, lens] { background_pass(lens); });
     }
-    return true;
+    c_.step_us += now_us() - t_begin;
+    return rc;
 }
 
-bool MetaRing::acquire(size_t bytes, char** host, char** dev) {
-    if (bytes > slot_bytes_ && !grow(bytes)) return false;
-    cur_ = (cur_ + 1) % kSlots;
-    if (pending_[cur_]) {
-        if (!hip_ok(hipEventSynchronize(ev_[cur_]), "hipEventSynchronize")) return false;
-        pending_[cur_] = false;
+// Runs on the helper thread between a step() and the next sync().  During that window the caller's
+// thread touches none of mapped_, held_, free_handles_, c_ (it validates launches against committed_),
+// and active_ is read-only for both.
+void KvMemory::background_pass(const std::vector<int64_t>& lens) {
+    const double t0 = now_us();
+    // 1. look-ahead (Sec. 6.1.1): the growth the coming iterations are known to need
+    for (int r = 0; r < B_; ++r) {
+        if (!active_[r] || lens[r] == 0) continue;
+        const int64_t ahead = lens[r] + lookahead_ < L_ ? lens[r] + lookahead_ : L_;
+        const int64_t grow = need(ahead) - mapped_[r];
+        if (grow > 0 && grow * nbuf_ <= free_now()) (void)map_rows(r, mapped_[r], mapped_[r] + grow, true);
     }
-    *host = host_ + static_cast<size_t>(cur_) * slot_bytes_;
-    *dev = dev_ + static_cast<size_t>(cur_) * slot_bytes_;
-    return true;
-}
-
-bool MetaRing::commit(size_t bytes, hipStream_t stream) {
-    char* h = host_ + static_cast<size_t>(cur_) * slot_bytes_;
-    char* d = dev_ + static_cast<size_t>(cur_) * slot_bytes_;
-    if (!hip_ok(hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, stream), "hipMemcpyAsync (index upload)")) return false;
-    if (!hip_ok(hipEventRecord(ev_[cur_], stream), "hipEventRecord")) return false;
-    pending_[cur_] = true;
-    return true;
-}
-
-// ---------------------------------------------------------------------------------------------
-
-bool KernelTimer::next(hipEvent_t* start, hipEvent_t* stop) {
-    Pair p{};
-    if (!spare.empty()) { p = spare.back(); spare.pop_back(); }
-    else {
-        if (!hip_ok(hipEventCreate(&p.a), "hipEventCreate")) return false;
-        if (!hip_ok(hipEventCreate(&p.b), "hipEventCreate")) return false;
+    if (policy_ == VATTN_POLICY_DEFERRED) {
+        const int cand = next_candidate();
+        // 2. threshold reclamation (Sec. 6.1.2): inactive ids give pages back only when the pool runs low
+        if (free_now() < reclaim_threshold_) {
+            for (int r = 0; r < B_ && free_now() < reclaim_threshold_; ++r) {
+                if (active_[r] || r == cand) continue;
+                while (mapped_[r] > 0 && free_now() < reclaim_threshold_) unmap_rows(r, mapped_[r] - 1);
+            }
+        }
+        // 3. eager allocation (Sec. 6.1.2): keep the reqId that will be handed out next backed
+        if (cand >= 0 && eager_ > mapped_[cand]) {
+            int64_t grow = eager_ - mapped_[cand];
+            const int64_t fit = free_now() / nbuf_;
+            if (grow > fit) grow = fit;
+            if (grow > 0) (void)map_rows(cand, mapped_[cand], mapped_[cand] + grow, true);
+        }
     }
-    open.push_back(p);
-    *start = p.a; *stop = p.b;
-    return true;
-}
-bool KernelTimer::collect(double* total_ms, int64_t* launches) {
-    double t = 0;
-    for (auto& p : open) {
-        if (!hip_ok(hipEventSynchronize(p.b), "hipEventSynchronize")) return false;
-        float ms = 0;
-        if (!hip_ok(hipEventElapsedTime(&ms, p.a, p.b), "hipEventElapsedTime")) return false;
-        t += ms;
-        spare.push_back(p);
-    }
-    if (total_ms) *total_ms = t;
-    if (launches) *launches = static_cast<int64_t>(open.size());
-    open.clear();
-    return true;
-}
-void KernelTimer::destroy() {
-    for (auto& p : open) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
-    for (auto& p : spare) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
-    open.clear(); spare.clear();
+    c_.background_us += now_us() - t0;
 }
 
 }  // namespace vattn

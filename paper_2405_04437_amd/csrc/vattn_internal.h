@@ -8,53 +8,17 @@
 #include <vector>
 
 #include "../../include/vattn.h"
+#include "kv_memory.h"
 
 namespace vattn {
 
-void set_error(const std::string& msg);
 bool hip_ok(hipError_t e, const char* what);  // records the error text and returns false on failure
 
-// ---------------------------------------------------------------------------------------------
-// Memory manager: 2N virtual reservations, a pool of physical page-group handles, per-reqId counts.
-// Follows Sec. 5 of the paper (virtual tensors, reqId indexing, init/alloc_reqid/free_reqid/step).
-// ---------------------------------------------------------------------------------------------
-class KvMemory {
-public:
-    ~KvMemory();
-    bool init(const vattn_config& cfg);
-    int alloc_reqid();
-    int free_reqid(int reqid);
-    int step(const int64_t* seq_lens, int count);
-
-    char* sub_tensor(int layer, int which, int reqid) const {
-        return base_[static_cast<size_t>(layer) * 2 + which] + static_cast<int64_t>(reqid) * S_;
-    }
-    char* buffer_base(int layer, int which) const { return base_[static_cast<size_t>(layer) * 2 + which]; }
-    bool valid_reqid(int r) const { return r >= 0 && r < B_; }
-    bool is_active(int r) const { return active_[r] != 0; }
-    int64_t mapped(int r) const { return mapped_[r]; }
-    int64_t mapped_tokens(int r) const { return mapped_[r] * G_ / T_; }
-    int64_t G() const { return G_; }
-    int64_t S() const { return S_; }
-    int64_t T() const { return T_; }
-    int64_t pool_total() const { return pool_total_; }
-    int64_t pool_free() const { return static_cast<int64_t>(free_handles_.size()); }
-    int64_t map_calls = 0, unmap_calls = 0;
-    double map_us = 0, unmap_us = 0;
-
-private:
-    bool map_rows(int r, int64_t from, int64_t to);  // page-group rows [from,to) of reqId r, all buffers
-    void unmap_rows(int r, int64_t keep);            // unmap rows [keep, mapped) and return handles
-    int N_ = 0, B_ = 0, device_ = 0;
-    uint32_t policy_ = 0;
-    int64_t L_ = 0, G_ = 0, S_ = 0, T_ = 0, pool_total_ = 0;
-    std::vector<char*> base_;                                     // 2N reservations of B*S bytes
-    std::vector<hipMemGenericAllocationHandle_t> free_handles_;   // created, unmapped
-    std::vector<std::vector<hipMemGenericAllocationHandle_t>> held_;  // per reqId: rows x 2N handles
-    std::vector<uint8_t> active_;
-    std::vector<int64_t> mapped_;
-    hipMemAccessDesc access_{};
-};
+// Driver-operation tables for the memory manager: HIP virtual-memory calls, and the statically backed
+// baseline (whole buffers from hipMalloc, mapping reduced to bookkeeping).
+const VmmOps& hip_vmm_ops();
+const VmmOps& hip_static_ops();
+bool vmm_microbench(int device, int64_t bytes, int count, double* out_us);
 
 // ---------------------------------------------------------------------------------------------
 // Pinned staging ring for the small index arrays every attention call uploads.
@@ -104,6 +68,7 @@ struct AppendArgs {
     char* k_base; char* v_base;             // buffer bases of the layer
     int64_t S;                              // bytes between consecutive reqIds
     int64_t row_bytes;                      // H*D*P
+    int64_t tok_stride;                     // bytes between consecutive tokens of the layer (H*D*P, or N*H*D*P when sliced)
     const int32_t* reqids; const int32_t* cu_q; const int32_t* kv_before;  // device, n / n+1 / n
     int n; int total_rows;
     int inline_meta;                        // 1: arrays are in InlineMeta as [reqids | kv_before | cu_q]
@@ -114,6 +79,7 @@ struct DecodeArgs {
     const void* q; void* o;                 // [n, Hq, D] bf16
     const char* k_base; const char* v_base; int64_t S;
     int Hq, H, D;
+    int row_stride;                         // bytes between consecutive tokens of the layer
     // Split-K partition: the contexts of all requests, cut into 32-token tiles, form one global tile
     // sequence (request-major).  Segment s owns tiles [s*tiles_per_seg, (s+1)*tiles_per_seg); a segment
     // that crosses a request boundary produces one partial per request it touches.  The partial of
@@ -134,6 +100,7 @@ struct PrefillArgs {
     const void* q; void* o;                 // [sum q_len, Hq, D] bf16
     const char* k_base; const char* v_base; int64_t S;
     int Hq, H, D;
+    int row_stride;                         // bytes between consecutive tokens of the layer
     const int32_t* reqids; const int32_t* cu_q; const int32_t* kv_lens;   // device
     const PrefillItem* items;               // device: 8 queues of items_per_xcd entries each
     int items_per_xcd; int n;

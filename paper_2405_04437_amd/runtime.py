@@ -29,12 +29,14 @@ class KvSession:
 
     def __init__(self, num_q_heads: int, num_kv_heads: int, head_dim: int, max_batch: int, max_ctx: int,
                  phys_budget_bytes: int, num_layers: int = 1, page_group_bytes: int = 0,
-                 policy: int = POLICY_SYNC_UNMAP, device: int = 0) -> None:
+                 policy: int = POLICY_SYNC_UNMAP, device: int = 0, flags: int = 0, lookahead_tokens: int = 0,
+                 eager_page_groups: int = 0, reclaim_threshold_page_groups: int = 0) -> None:
         if not torch.cuda.is_available():
             raise RuntimeError("KvSession needs a GPU: the HIP path has no CPU fallback")
         torch.cuda.set_device(device)
         self.va = Vattn(num_layers, max_batch, max_ctx, num_q_heads, num_kv_heads, head_dim, phys_budget_bytes,
-                        page_group_bytes, 2, device, policy)
+                        page_group_bytes, 2, device, policy, flags, lookahead_tokens, eager_page_groups,
+                        reclaim_threshold_page_groups)
         self.Hq, self.H, self.D = num_q_heads, num_kv_heads, head_dim
         self.B = max_batch
         self.num_layers = num_layers

@@ -1,0 +1,131 @@
+// Host-only driver of the KV memory manager: the driver-operation table is filled with bookkeeping
+// fakes (no GPU runtime), commands come from stdin, the manager's state goes to stdout.  Built with a
+// plain C++ compiler (optionally with a thread sanitizer) by tests/test_host_manager.py.
+//
+// Commands:  init N B L H D G pool flags lookahead eager threshold | a | f <reqid> | s <len>*B | q | quit
+#include <cstdio>
+#include <iostream>
+#include <map>
+#include <mutex>
+#include <set>
+#include <sstream>
+
+#include "../../paper_2405_04437_amd/csrc/kv_memory.h"
+
+namespace {
+
+// The fakes keep their own record of what is mapped where, and fail on anything the real driver would
+// reject: mapping over a mapped range, mapping a handle twice, unmapping what is not mapped.
+std::mutex g_mu;
+std::map<uintptr_t, uint64_t> g_mapped;   // va -> handle
+std::set<uint64_t> g_in_use, g_alive;
+std::set<uintptr_t> g_access;
+uintptr_t g_next_va = uintptr_t{1} << 40;
+uint64_t g_next_handle = 1;
+long g_violations = 0;
+size_t g_G = 0;
+
+bool bad(const char* what) { ++g_violations; vattn::set_error(what); return false; }
+
+bool f_bind(int) { return true; }
+bool f_gran(int, size_t* b) { *b = 4096; return true; }
+bool f_reserve(void** va, size_t bytes, size_t align) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_next_va = (g_next_va + align - 1) / align * align;
+    *va = reinterpret_cast<void*>(g_next_va);
+    g_next_va += bytes;
+    return true;
+}
+bool f_va_free(void*, size_t) { return true; }
+bool f_create(uint64_t* h, size_t bytes, int) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_G = bytes;
+    *h = g_next_handle++;
+    g_alive.insert(*h);
+    return true;
+}
+bool f_release(uint64_t h) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (g_in_use.count(h)) return bad("release of a mapped handle");
+    return g_alive.erase(h) == 1 ? true : bad("release of an unknown handle");
+}
+bool f_map(void* va, size_t bytes, uint64_t h) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    const uintptr_t a = reinterpret_cast<uintptr_t>(va);
+    if (bytes != g_G || a % g_G) return bad("map: wrong size or alignment");
+    if (!g_alive.count(h)) return bad("map: unknown handle");
+    if (g_in_use.count(h)) return bad("map: handle already mapped");
+    if (g_mapped.count(a)) return bad("map: range already mapped");
+    g_mapped[a] = h;
+    g_in_use.insert(h);
+    return true;
+}
+bool f_access(void* va, size_t bytes, int) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    const uintptr_t a = reinterpret_cast<uintptr_t>(va);
+    for (uintptr_t x = a; x < a + bytes; x += g_G) {
+        if (!g_mapped.count(x)) return bad("set_access over an unmapped range");
+        g_access.insert(x);
+    }
+    return true;
+}
+bool f_unmap(void* va, size_t bytes) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    const uintptr_t a = reinterpret_cast<uintptr_t>(va);
+    auto it = g_mapped.find(a);
+    if (bytes != g_G || it == g_mapped.end()) return bad("unmap of an unmapped range");
+    g_in_use.erase(it->second);
+    g_mapped.erase(it);
+    g_access.erase(a);
+    return true;
+}
+bool f_sync() { return true; }
+
+}  // namespace
+
+int main() {
+    const vattn::VmmOps ops{f_bind, f_gran, f_reserve, f_va_free, f_create, f_release, f_map, f_access, f_unmap, f_sync};
+    vattn::KvMemory* mem = nullptr;
+    vattn_config cfg{};
+    std::string line;
+    while (std::getline(std::cin, line)) {
+        std::istringstream in(line);
+        std::string cmd;
+        in >> cmd;
+        if (cmd == "init") {
+            long long L, G, pool, thr;
+            unsigned flags;
+            in >> cfg.num_layers >> cfg.max_batch >> L >> cfg.num_kv_heads >> cfg.head_dim >> G >> pool >> flags >> cfg.lookahead_tokens >> cfg.eager_page_groups >> thr;
+            cfg.max_ctx = L; cfg.num_q_heads = cfg.num_kv_heads; cfg.elem_bytes = 2; cfg.page_group_bytes = G;
+            cfg.phys_budget_bytes = pool * G; cfg.flags = flags; cfg.reclaim_threshold_page_groups = thr;
+            delete mem;
+            mem = new vattn::KvMemory();
+            const bool ok = mem->init(cfg, ops);
+            std::printf("%d\n", ok ? 0 : -1);
+            if (!ok) { delete mem; mem = nullptr; }
+        } else if (cmd == "a") {
+            std::printf("%d\n", mem->alloc_reqid());
+        } else if (cmd == "f") {
+            int r; in >> r;
+            std::printf("%d\n", mem->free_reqid(r));
+        } else if (cmd == "s") {
+            std::vector<int64_t> lens;
+            long long x;
+            while (in >> x) lens.push_back(x);
+            std::printf("%d\n", mem->step(lens.data(), static_cast<int>(lens.size())));
+        } else if (cmd == "q") {
+            const vattn::KvMemory::Counters c = mem->counters();
+            std::printf("free %lld maps %lld unmaps %lld sync %lld bg %lld S %lld viol %ld live %zu |",
+                        (long long)mem->pool_free(), (long long)c.map_calls, (long long)c.unmap_calls, (long long)c.sync_map_calls,
+                        (long long)c.background_map_calls, (long long)mem->S(), g_violations, g_mapped.size());
+            for (int r = 0; r < cfg.max_batch; ++r) std::printf(" %d:%lld:%lld", mem->is_active(r) ? 1 : 0, (long long)mem->mapped(r), (long long)mem->mapped_committed(r));
+            std::printf("\n");
+        } else if (cmd == "quit") {
+            break;
+        }
+        std::fflush(stdout);
+    }
+    delete mem;
+    std::printf("end viol %ld live %zu alive %zu\n", g_violations, g_mapped.size(), g_alive.size());
+    return g_violations ? 1 : 0;
+}

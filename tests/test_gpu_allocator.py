@@ -140,3 +140,70 @@ def test_mapped_ranges_hold_data_across_growth_and_reuse():
     assert np.array_equal(back, tail)
     assert base == va.kv_ptr(0, 0, 0)
     va.destroy()
+
+
+@pytest.mark.parametrize("sliced", [False, True])
+@pytest.mark.parametrize("policy", ["sync", "deferred"])
+def test_background_and_sliced_traces_match_model_bit_exactly(policy, sliced):
+    """The latency-hiding background thread (look-ahead, threshold reclamation, eager allocation) and the
+    all-layers-in-one-buffer layout reach, at every call boundary, exactly the state the model computes."""
+    import paper_2405_04437_amd as P
+
+    sh = W.YI_6B
+    N, B, L, G = 2, 10, 5000, 64 * KiB
+    pool = 240 if not sliced else 230
+    look, eager, thr = 1, 2, 40
+    pol = P.POLICY_DEFERRED if policy == "deferred" else P.POLICY_SYNC_UNMAP
+    flags = P.FLAG_BACKGROUND | (P.FLAG_TENSOR_SLICING if sliced else 0)
+    va = P.Vattn(N, B, L, sh.num_q_heads, sh.num_kv_heads, sh.head_dim, pool * G, G, policy=pol, flags=flags,
+                 lookahead_tokens=look, eager_page_groups=eager, reclaim_threshold_page_groups=thr)
+    model = AllocatorModel(N, B, L, sh.num_kv_heads, sh.head_dim, 2, G, pool, policy, sliced=sliced, background=True,
+                           lookahead_tokens=look, eager_page_groups=eager, reclaim_threshold=thr)
+    _compare(va, model, B)
+    rng = np.random.default_rng(5)
+    lens = [0] * B
+    fails = 0
+    for i in range(260):
+        op = int(rng.integers(0, 10))
+        if op == 0:
+            a, b = va.alloc_reqid(), model.alloc_reqid()
+            assert a == b
+            if a >= 0:
+                lens[a] = int(rng.integers(1, 2500))
+        elif op == 1:
+            act = [r for r in range(B) if model.active[r]]
+            if act:
+                r = int(rng.choice(act))
+                assert va.free_reqid(r) == model.free_reqid(r) == 0
+                lens[r] = 0
+        else:
+            trial = [min(x + 1, L) if x else 0 for x in lens]
+            ra, rb = va.step(trial), model.step(trial)
+            assert ra == rb
+            if ra == 0:
+                lens = trial
+            else:
+                fails += 1
+        _compare(va, model, B)
+    sync_maps, bg_maps, step_us, bg_us, wait_us = va.step_counters()
+    assert (sync_maps, bg_maps) == (model.sync_map_calls, model.background_map_calls)
+    assert bg_maps > 0 and bg_us > 0
+    mc, uc, _, _ = va.counters()
+    assert (mc, uc) == (model.map_calls, model.unmap_calls)
+    # sliced: layer n of a request starts n*H*D*P bytes into its sub-tensor
+    if sliced:
+        assert va.kv_ptr(1, 0, 3) - va.kv_ptr(0, 0, 3) == sh.num_kv_heads * sh.head_dim * 2
+        assert va.kv_ptr(0, 0, 4) - va.kv_ptr(0, 0, 3) == model.S
+    va.destroy()
+
+
+def test_vmm_microbench_reports_every_call():
+    import paper_2405_04437_amd as P
+
+    for G, count in ((64 * KiB, 64), (2 * MiB, 32)):
+        us = P.vmm_microbench(G, count)
+        assert len(us) == 9 and all(x > 0 for x in us)
+    with pytest.raises(P.VattnError):
+        P.vmm_microbench(1000, 4)          # not a multiple of the granularity
+    with pytest.raises(P.VattnError):
+        P.vmm_microbench(64 * KiB, 0)
