@@ -90,8 +90,10 @@ typedef struct {
 
 /* init (Table 4; Sec. 5.3.1): reserves 2N virtual buffers of B*S bytes each, S = L*H*D*P rounded
  * up to the page-group size (Sec. 5.1.3) - with TENSOR_SLICING, 2 buffers and S = L*N*H*D*P - and
- * creates the physical page-group pool WITHOUT mapping any of it.  *out receives the context.  Fails if the device lacks virtual-memory support, the
- * configuration is invalid, or the pool cannot be created. */
+ * creates the physical page-group pool WITHOUT mapping any of it.  *out receives the context.
+ * Fails if the device lacks virtual-memory support, the configuration is invalid, the pool cannot
+ * be created, or it holds more page-groups than the process can keep mapped (each mapped
+ * page-group is one memory mapping of the process; Linux caps them at vm.max_map_count). */
 int vattn_init(const vattn_config* cfg /*host*/, vattn_ctx** out /*host*/);
 
 /* Unmaps and releases everything, frees the reservations and the context.  The caller must have
@@ -151,7 +153,7 @@ int vattn_sync(vattn_ctx* ctx);
  * the paper): creates, maps, touches and tears down `count` page-groups of `bytes` each on `device`
  * and writes average microseconds per call to out_us[9] (host):
  *   0 hipMemAddressReserve   1 hipMemCreate   2 hipMemMap   3 hipMemSetAccess (one page-group per call)
- *   4 hipMemSetAccess, one call over all page-groups (total)   5 hipMemUnmap   6 hipMemRelease
+ *   4 hipMemSetAccess, ONE call over all page-groups freshly mapped again (total)   5 hipMemUnmap   6 hipMemRelease
  *   7 hipMemAddressFree      8 a kernel writing every mapped byte once (total).
  * Needs no context.  `bytes` must be a multiple of the allocation granularity. */
 int vattn_vmm_microbench(int device, int64_t bytes, int count, double* out_us /*host*/);

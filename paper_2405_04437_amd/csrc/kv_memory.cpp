@@ -113,6 +113,13 @@ bool KvMemory::init(const vattn_config& c, const VmmOps& ops) {
     S_ = (L_ * Tbuf_ + G_ - 1) / G_ * G_;
     pool_total_ = c.phys_budget_bytes / G_;
     if (pool_total_ < 0) { set_error("init: negative physical budget"); return false; }
+    const int64_t limit = ops_.mapping_limit ? ops_.mapping_limit() : 0;
+    if (limit > 0 && pool_total_ > limit) {
+        set_error("init: the pool has " + std::to_string(pool_total_) + " page-groups, but this process can keep only about " +
+                  std::to_string(limit) + " mapped (every mapped page-group is one memory mapping of the process and the "
+                  "operating system caps their number); use larger page-groups");
+        return false;
+    }
 
     const size_t buf_bytes = static_cast<size_t>(B_) * static_cast<size_t>(S_);
     base_.assign(static_cast<size_t>(nbuf_), nullptr);

@@ -34,6 +34,7 @@ struct VmmOps {
     bool (*set_access)(void* va, size_t bytes, int device);        // read/write for the device
     bool (*unmap)(void* va, size_t bytes);
     bool (*device_sync)();                                         // wait for all work queued on the device
+    int64_t (*mapping_limit)();                                    // page-groups one process can keep mapped (0 = no limit)
 };
 
 // One helper thread that runs one task at a time.  submit() and wait() are called from the thread

@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Measurements around the memory manager on one MI355X, printed as markdown:
+
+  1. per-call latency of the HIP virtual-memory API at several page-group sizes (the analogue of the
+     paper's table of VMM API latencies) and the allocation bandwidth that follows from it (the
+     analogue of its allocation-bandwidth table);
+  2. page-group size effect: the same decode kernel over KV mapped with 64 KiB / 2 MiB page-groups and
+     over a statically backed hipMalloc buffer (the paper's "no TLB thrashing with small pages" check);
+  3. latency hiding: a decode loop whose requests cross a page-group boundary every few steps, with
+     step() mapping synchronously vs the background thread mapping one step ahead (per-iteration step()
+     time, its maximum, and where the map calls happened);
+  4. deferred reclamation + eager allocation: time from "request arrives" to "prefill may start"
+     (alloc_reqid + step) with pages unmapped on free, deferred, and deferred + eager.
+
+Everything runs through the C ABI (paper_2405_04437_amd.binding); no result is checked here - parity lives in
+tests/.  Usage: python paper_2405_04437_amd/vmm_report.py [--quick]
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+KiB, MiB = 1024, 1024 * 1024
+CALLS = ["hipMemAddressReserve", "hipMemCreate", "hipMemMap", "hipMemSetAccess (per page-group)",
+         "hipMemSetAccess (one call, all)", "hipMemUnmap", "hipMemRelease", "hipMemAddressFree", "touch kernel (all)"]
+
+
+def api_latency(P, quick):
+    sizes = [(4 * KiB, 256), (64 * KiB, 256), (256 * KiB, 256), (2 * MiB, 256), (32 * MiB, 32)]
+    rows = {}
+    for G, count in sizes:
+        if quick:
+            count = min(count, 32)
+        best = None
+        for _ in range(3):
+            us = P.vmm_microbench(G, count)
+            best = us if best is None else [min(a, b) for a, b in zip(best, us)]
+        rows[G] = (count, best)
+    print("## 1. HIP virtual-memory API latency (microseconds per call, best of 3 runs)\n")
+    print("| call | " + " | ".join(f"{G // KiB} KiB" for G, _ in sizes) + " |")
+    print("|---|" + "---|" * len(sizes))
+    for i, name in enumerate(CALLS):
+        print(f"| {name} | " + " | ".join(f"{rows[G][1][i]:.1f}" for G, _ in sizes) + " |")
+    print("\nPage-groups per run: " + ", ".join(f"{G // KiB} KiB x {rows[G][0]}" for G, _ in sizes))
+    print("\nAllocation bandwidth = page-group bytes / (hipMemMap + hipMemSetAccess per page-group):\n")
+    print("| page-group | us per page-group | GB/s |")
+    print("|---|---|---|")
+    for G, _ in sizes:
+        t = rows[G][1][2] + rows[G][1][3]
+        print(f"| {G // KiB} KiB | {t:.1f} | {G / t / 1e3:.2f} |")
+    print()
+
+
+def _decode_session(P, torch, W, G, flags, n=32, ctx=8192, layers=2):
+    from paper_2405_04437_amd.runtime import KvSession
+
+    shape = W.YI_6B
+    max_ctx = ctx + 4096
+    per_req = (max_ctx * shape.token_bytes + G - 1) // G * G
+    s = KvSession(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, n + 4, max_ctx, per_req * 2 * layers * (n + 4), layers, G,
+                  P.POLICY_DEFERRED, flags=flags, lookahead_tokens=1)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(1)
+    ids = [s.admit(ctx) for _ in range(n)]
+    s.step()
+    for r in ids:
+        for layer in range(layers):
+            k = torch.randn((ctx, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+            s.append(layer, k, k, [r], [0, ctx], [0])
+    return s, ids, shape, gen
+
+
+def page_size_effect(P, torch, W, quick):
+    print("## 2. Page-group size vs decode kernel bandwidth (32 requests x 8192 tokens, Yi-6B shape)\n")
+    print("| backing | split-K kernel us | GB/s |")
+    print("|---|---|---|")
+    for name, G, flags in (("VMM, 64 KiB page-groups", 64 * KiB, 0), ("VMM, 256 KiB page-groups", 256 * KiB, 0),
+                           ("VMM, 2 MiB page-groups", 2 * MiB, 0), ("hipMalloc (static backing)", 2 * MiB, P.FLAG_STATIC_BACKING)):
+        s, ids, shape, gen = _decode_session(P, torch, W, G, flags)
+        n, ctx = len(ids), 8192
+        q = torch.randn((n, shape.num_q_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+        o = torch.empty_like(q)
+        lens = [ctx] * n
+        ws = s.workspace(lens)
+        scale = W.softmax_scale(shape.head_dim)
+        for i in range(20):
+            s.decode(i % 2, q, ids, lens, scale, out=o, ws=ws)
+        torch.cuda.synchronize()
+        s.va.set_timing(True); s.va.kernel_time(0)
+        for i in range(100):
+            s.decode(i % 2, q, ids, lens, scale, out=o, ws=ws)
+        torch.cuda.synchronize()
+        ms, cnt = s.va.kernel_time(0)
+        us = ms * 1e3 / cnt
+        nbytes = n * ctx * 2 * shape.token_bytes
+        print(f"| {name} | {us:.1f} | {nbytes / us / 1e3:.0f} |")
+        s.close()
+    print()
+
+
+def latency_hiding(P, torch, W, quick):
+    print("## 3. Synchronous step() vs background look-ahead (decode loop, 32 requests, 64 KiB page-groups)\n")
+    print("Every request crosses a page-group boundary every 64 tokens; the 32 requests start at staggered offsets, so")
+    print("every other step one request needs a new page-group in each of the 2N buffers.  An iteration is step(), the")
+    print("KV append and the decode attention of ALL N layers (no other model work: the shortest iteration a serving")
+    print("loop could have, i.e. the least time to hide the mapping in), then a stream synchronisation.\n")
+    print("| N layers | mode | iteration us | step() mean us | p99 us | max us | map calls in step() | in background | wait for pass us/step |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    steps = 200 if quick else 1000
+    for layers in (2, 8):
+        for name, flags in (("synchronous", 0), ("background thread, look-ahead 1", P.FLAG_BACKGROUND)):
+            s, ids, shape, gen = _decode_session(P, torch, W, 64 * KiB, flags, ctx=4096, layers=layers)
+            n = len(ids)
+            lens = np.array([4096 + 2 * i for i in range(n)], dtype=np.int64)
+            seq = np.zeros(s.B, dtype=np.int64)
+            seq[ids] = lens
+            assert s.va.step(seq) == 0
+            q = torch.randn((n, shape.num_q_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+            knew = torch.randn((n, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+            o = torch.empty_like(q)
+            ws = s.workspace([int(x) + steps + 8 for x in lens])
+            scale = W.softmax_scale(shape.head_dim)
+            cu = np.arange(n + 1, dtype=np.int32)
+            ids_np = np.array(ids, dtype=np.int32)
+            c0 = s.va.step_counters()
+            times = []
+            stream = s.stream
+            t_loop = time.perf_counter()
+            for i in range(steps):
+                seq[ids] = lens + 1
+                t0 = time.perf_counter()
+                assert s.va.step(seq) == 0
+                times.append((time.perf_counter() - t0) * 1e6)
+                for layer in range(layers):
+                    s.va.append_kv(layer, stream, knew, knew, ids_np, cu, lens)
+                lens += 1
+                for layer in range(layers):
+                    s.va.attn_decode(layer, stream, q, o, ids_np, lens, scale, ws, ws.numel())
+                torch.cuda.current_stream().synchronize()
+            it_us = (time.perf_counter() - t_loop) * 1e6 / steps
+            c1 = s.va.step_counters()
+            t = np.array(times)
+            print(f"| {layers} | {name} | {it_us:.0f} | {t.mean():.1f} | {np.percentile(t, 99):.1f} | {t.max():.1f} | {c1[0] - c0[0]} | {c1[1] - c0[1]} | {(c1[4] - c0[4]) / steps:.1f} |")
+            s.close()
+    print()
+
+
+def prefill_admission(P, torch, W, quick):
+    print("## 4. Admitting a new request: alloc_reqid + step() until its prompt is backed (2048-token prompt, Llama-3-8B shape, 2 layers)\n")
+    print("A request finishes (free_reqid), the next one arrives.  64 KiB page-groups: 64 page-groups per buffer, 256 in all.\n")
+    print("| policy | admit mean us | max us | map calls per admission (critical path) | free_reqid mean us |")
+    print("|---|---|---|---|---|")
+    from paper_2405_04437_amd.binding import Vattn
+
+    shape = W.LLAMA3_8B
+    G, layers, B, prompt = 64 * KiB, 2, 8, 2048
+    need = prompt * shape.token_bytes // G
+    rounds = 10 if quick else 40
+    for name, policy, flags, eager in (("unmap on free (synchronous)", P.POLICY_SYNC_UNMAP, 0, 0),
+                                       ("deferred reclamation", P.POLICY_DEFERRED, 0, 0),
+                                       ("deferred + background eager allocation", P.POLICY_DEFERRED, P.FLAG_BACKGROUND, need)):
+        va = Vattn(layers, B, 4096, shape.num_q_heads, shape.num_kv_heads, shape.head_dim, 4 * need * 2 * layers * G, G,
+                   policy=policy, flags=flags, lookahead_tokens=1, eager_page_groups=eager)
+        seq = np.zeros(B, dtype=np.int64)
+        # a resident request keeps the loop honest (step() always has someone to look at)
+        r0 = va.alloc_reqid(); seq[r0] = 100
+        assert va.step(seq) == 0
+        times, frees, c0 = [], [], 0
+        first = True
+        for _ in range(rounds):
+            va.sync()                      # the previous pass has had an iteration's time to finish
+            t0 = time.perf_counter()
+            r = va.alloc_reqid()
+            seq[r] = prompt
+            assert va.step(seq) == 0
+            dt = (time.perf_counter() - t0) * 1e6
+            if not first:
+                times.append(dt)
+            else:                          # the very first admission always maps from scratch: not counted
+                c0 = va.step_counters()[0]
+            first = False
+            va.sync()
+            seq[r] = 0
+            t0 = time.perf_counter()
+            assert va.free_reqid(r) == 0
+            frees.append((time.perf_counter() - t0) * 1e6)
+            assert va.step(seq) == 0       # an iteration without the request: the background pass prepares the next id
+        c1 = va.step_counters()[0]
+        t = np.array(times)
+        print(f"| {name} | {t.mean():.1f} | {t.max():.1f} | {(c1 - c0) / (rounds - 1):.1f} | {np.mean(frees):.1f} |")
+        va.destroy()
+    print()
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--quick", action="store_true")
+    args = ap.parse_args()
+    import torch
+
+    if not torch.cuda.is_available():
+        print("vmm_report.py needs a GPU", file=sys.stderr)
+        return 1
+    import paper_2405_04437_amd as P
+    import workloads as W
+
+    torch.cuda.set_stream(torch.cuda.Stream())
+    print(f"# Memory-manager measurements on {torch.cuda.get_device_name(0)}\n")
+    print("Command: `python paper_2405_04437_amd/vmm_report.py" + (" --quick" if args.quick else "") + "`\n")
+    api_latency(P, args.quick)
+    page_size_effect(P, torch, W, args.quick)
+    latency_hiding(P, torch, W, args.quick)
+    prefill_admission(P, torch, W, args.quick)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -84,7 +84,7 @@ bool f_sync() { return true; }
 }  // namespace
 
 int main() {
-    const vattn::VmmOps ops{f_bind, f_gran, f_reserve, f_va_free, f_create, f_release, f_map, f_access, f_unmap, f_sync};
+    const vattn::VmmOps ops{f_bind, f_gran, f_reserve, f_va_free, f_create, f_release, f_map, f_access, f_unmap, f_sync, nullptr};
     vattn::KvMemory* mem = nullptr;
     vattn_config cfg{};
     std::string line;

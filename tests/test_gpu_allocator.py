@@ -207,3 +207,18 @@ def test_vmm_microbench_reports_every_call():
         P.vmm_microbench(1000, 4)          # not a multiple of the granularity
     with pytest.raises(P.VattnError):
         P.vmm_microbench(64 * KiB, 0)
+
+
+def test_pool_larger_than_the_mapping_limit_is_refused():
+    """Each mapped page-group is one memory mapping of the process; a pool that could exceed the system's
+    cap on mappings is rejected at init instead of failing inside the driver later."""
+    import paper_2405_04437_amd as P
+
+    with open("/proc/sys/vm/max_map_count") as f:
+        cap = int(f.read())
+    G = 4 * KiB
+    with pytest.raises(P.VattnError, match="page-groups"):
+        P.Vattn(1, 4, 1 << 20, 8, 2, 64, (cap + 10) * G, G)
+    # the statically backed baseline maps nothing and is not limited
+    va = P.Vattn(1, 2, 4096, 8, 2, 64, (cap + 10) * G, G, flags=P.FLAG_STATIC_BACKING)
+    va.destroy()
