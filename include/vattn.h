@@ -92,8 +92,9 @@ typedef struct {
  * up to the page-group size (Sec. 5.1.3) - with TENSOR_SLICING, 2 buffers and S = L*N*H*D*P - and
  * creates the physical page-group pool WITHOUT mapping any of it.  *out receives the context.
  * Fails if the device lacks virtual-memory support, the configuration is invalid, the pool cannot
- * be created, or it holds more page-groups than the process can keep mapped (each mapped
- * page-group is one memory mapping of the process; Linux caps them at vm.max_map_count). */
+ * be created, or it holds more page-groups than the library allows: the smaller of 32768 and what
+ * the process can keep mapped (each mapped page-group is one memory mapping of the process; Linux
+ * caps them at vm.max_map_count).  Larger caches need larger page-groups. */
 int vattn_init(const vattn_config* cfg /*host*/, vattn_ctx** out /*host*/);
 
 /* Unmaps and releases everything, frees the reservations and the context.  The caller must have

@@ -63,10 +63,13 @@ bool vmm_set_access(void* va, size_t bytes, int device) {
 }
 bool vmm_unmap(void* va, size_t bytes) { return hip_ok(hipMemUnmap(va, bytes), "hipMemUnmap"); }
 
-// Every mapped page-group is a separate memory mapping of the process, and Linux caps those per
-// process (vm.max_map_count, 65530 by default).  Running into the cap was seen to crash inside the
-// runtime rather than fail cleanly, so the pool size is checked against it up front, with room left for
-// the mappings of the rest of the process.
+// How many page-group handles one pool may hold.  Two bounds, the smaller wins:
+//  * every mapped page-group is a separate memory mapping of the process, and Linux caps those per
+//    process (vm.max_map_count, 65530 by default); room is left for the rest of the process;
+//  * pools of 65 536 handles and more were seen to crash the process inside the runtime on MI355X
+//    (with 4 KiB and with 64 KiB handles, during creation or mapping), while 27 648 handles worked;
+//    until that is understood the library refuses more than 32 768.
+// Larger caches need larger page-groups: 32 768 x 2 MiB = 64 GiB, x 16 MiB = 512 GiB.
 int64_t vmm_mapping_limit() {
     long v = 65530;
     if (FILE* f = std::fopen("/proc/sys/vm/max_map_count", "r")) {
@@ -75,7 +78,8 @@ int64_t vmm_mapping_limit() {
         std::fclose(f);
     }
     const long headroom = 16384;
-    return v > 2 * headroom ? v - headroom : v / 2;
+    const long by_mappings = v > 2 * headroom ? v - headroom : v / 2;
+    return by_mappings < 32768 ? by_mappings : 32768;
 }
 int64_t no_mapping_limit() { return 0; }
 

@@ -115,9 +115,9 @@ bool KvMemory::init(const vattn_config& c, const VmmOps& ops) {
     if (pool_total_ < 0) { set_error("init: negative physical budget"); return false; }
     const int64_t limit = ops_.mapping_limit ? ops_.mapping_limit() : 0;
     if (limit > 0 && pool_total_ > limit) {
-        set_error("init: the pool has " + std::to_string(pool_total_) + " page-groups, but this process can keep only about " +
-                  std::to_string(limit) + " mapped (every mapped page-group is one memory mapping of the process and the "
-                  "operating system caps their number); use larger page-groups");
+        set_error("init: the pool has " + std::to_string(pool_total_) + " page-groups, but the limit is " +
+                  std::to_string(limit) + " (every mapped page-group is one memory mapping of the process, the operating "
+                  "system caps their number, and very large handle counts are not safe on this platform); use larger page-groups");
         return false;
     }
 

@@ -104,9 +104,9 @@ def page_size_effect(P, torch, W, quick):
 
 
 def latency_hiding(P, torch, W, quick):
-    print("## 3. Synchronous step() vs background look-ahead (decode loop, 32 requests, 64 KiB page-groups)\n")
-    print("Every request crosses a page-group boundary every 64 tokens; the 32 requests start at staggered offsets, so")
-    print("every other step one request needs a new page-group in each of the 2N buffers.  An iteration is step(), the")
+    print("## 3. Synchronous step() vs background look-ahead (decode loop, 32 requests, 256 KiB page-groups)\n")
+    print("Every request crosses a page-group boundary every 256 tokens; the 32 requests start at staggered offsets, so")
+    print("every 8th step one request needs a new page-group in each of the 2N buffers.  An iteration is step(), the")
     print("KV append and the decode attention of ALL N layers (no other model work: the shortest iteration a serving")
     print("loop could have, i.e. the least time to hide the mapping in), then a stream synchronisation.\n")
     print("| N layers | mode | iteration us | step() mean us | p99 us | max us | map calls in step() | in background | wait for pass us/step |")
@@ -114,9 +114,9 @@ def latency_hiding(P, torch, W, quick):
     steps = 200 if quick else 1000
     for layers in (2, 8):
         for name, flags in (("synchronous", 0), ("background thread, look-ahead 1", P.FLAG_BACKGROUND)):
-            s, ids, shape, gen = _decode_session(P, torch, W, 64 * KiB, flags, ctx=4096, layers=layers)
+            s, ids, shape, gen = _decode_session(P, torch, W, 256 * KiB, flags, ctx=4096, layers=layers)
             n = len(ids)
-            lens = np.array([4096 + 2 * i for i in range(n)], dtype=np.int64)
+            lens = np.array([4096 + 8 * i for i in range(n)], dtype=np.int64)
             seq = np.zeros(s.B, dtype=np.int64)
             seq[ids] = lens
             assert s.va.step(seq) == 0
