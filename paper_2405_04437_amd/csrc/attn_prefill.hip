@@ -6,8 +6,8 @@
 //
 // gfx950 mapping
 //  * One workgroup (4 waves) owns 128 query rows of one query head; each wave owns 32 rows.  KV is
-//    walked in tiles of 64 tokens, staged in LDS (double buffered; global loads for tile t+1 are in
-//    flight in registers while tile t is being multiplied).
+//    walked in tiles of 64 tokens, double buffered in LDS; tile t+1 travels from global memory straight
+//    into LDS (buffer loads with the LDS bit) while tile t is being multiplied.
 //  * Both contractions use v_mfma_f32_32x32x16_bf16.  Scores are produced transposed,
 //    S^T = K Q^T (tokens x rows): a lane then owns ONE query row, so the running max / sum are
 //    per-lane scalars (one cross-lane exchange per tile), and exp(S^T) is already laid out as the B
@@ -45,21 +45,27 @@ constexpr int kRsrcWord3 = 0x00020000;
 
 template <int D> struct PGeo {
     static constexpr int RB = D * 2;                         // bytes per head row
-    static constexpr int KSTR = RB + 16;                     // K row stride in LDS
-    static constexpr int VSTR = RB + 64;                     // V row stride in LDS
-    static constexpr int LPR = RB / 16;                      // lanes per row for global loads
-    static constexpr int RPI = kThreads / LPR;               // rows per load instruction
-    static constexpr int NL = kBN / RPI;                     // load instructions per tile per tensor
-    static constexpr int BUF = kBN * (KSTR + VSTR);          // one K+V stage
+    static constexpr int CH = RB / 16;                       // 16-byte chunks per row
+    static constexpr int RPW = 1024 / RB;                    // rows one wave-wide 16 B/lane load covers
+    static constexpr int NLW = kBN / 4 / RPW;                // such loads per wave, per tile and tensor
+    static constexpr int KV = kBN * RB;                      // one K (or V) tile in LDS, rows unpadded
+    static constexpr int BUF = 2 * KV;                       // one K+V stage
     static constexpr int LDS = 2 * BUF;
+    // Rows are stored unpadded (the loads below write LDS directly, 1 KiB contiguous per instruction), so
+    // bank conflicts are avoided by permuting the 16-byte chunks inside each row instead: chunk c of row r
+    // is stored at chunk position c ^ swz(r).  swz is even (32-byte pairs stay adjacent for the
+    // transposing reads) and takes 8 (D = 128) or 4 (D = 64) different values over any run of rows that
+    // falls on the same banks.
+    __device__ static constexpr int swz(int row) { return (((row * RB / 256) & 7) << 1) & (CH - 1); }
 };
+
+typedef __attribute__((address_space(3))) void* lds_ptr;
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
     using G = PGeo<D>;
-    constexpr int QB = 1;                      // 32-row query blocks per wave (the wide kernel has two)
-    constexpr int BM = 128 * QB;               // query rows per workgroup
-    constexpr int WR = 32 * QB;                // query rows per wave
+    constexpr int BM = 128;                    // query rows per workgroup
+    constexpr int WR = 32;                     // query rows per wave
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform per wave: keeps row/tile arithmetic scalar
@@ -87,89 +93,86 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
     const char* kp = a.k_base + sub;
     const char* vp = a.v_base + sub;
 
-    // Q^T as B operand: lane (n = l%32, h = l/32) holds Q[row n][ks*16 + h*8 .. +8], per query block
+    // Q^T as B operand: lane (n = l%32, h = l/32) holds Q[row n][ks*16 + h*8 .. +8]
     const int row_lo = q0 + w * WR;               // first query row of this wave
-    int my_row[QB];
-    bf16x8 qb[QB][D / 16];
-#pragma unroll
-    for (int qa = 0; qa < QB; ++qa) {
-        my_row[qa] = row_lo + qa * 32 + (l & 31);
-        const int qr = min(my_row[qa], q_len - 1);
+    const int my_row = row_lo + (l & 31);
+    bf16x8 qb[D / 16];
+    {
+        const int qr = min(my_row, q_len - 1);
         const char* qrow = static_cast<const char*>(a.q) + ((static_cast<int64_t>(q_begin) + qr) * a.Hq + head) * G::RB;
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks)
-            qb[qa][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + ks * 32 + (l >> 5) * 16));
+            qb[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + ks * 32 + (l >> 5) * 16));
     }
 
-    const int ld_row = tid / G::LPR;
-    const int ld_col = (tid % G::LPR) * 16;
-    // Global addressing: each tile of K and V is a raw buffer resource whose 64-bit base is scalar
-    // arithmetic (sub-tensors of any size are addressable); the loads add one per-lane offset, the same
-    // for the whole kernel, and a scalar offset per instruction.  num_records ends at the last row of
-    // the context: rows past it fail the hardware range check, return zeros and touch nothing, so no
-    // byte beyond what step() has mapped is read (their scores are masked).
-    const int lane_off = ld_row * rs32 + ld_col;
-    // One register set stages the next tile: it is requested right after the score multiplies of tile t
-    // have been issued and written to the other LDS buffer at the end of the iteration.  The issue is
-    // unconditional (a tile index past the end is out of range for every lane and loads zeros without
-    // touching memory) and sits at one place in the loop, which lets the compiler keep the loads in
-    // flight across the softmax and the second contraction.
-    u32x4 kregA[G::NL], vregA[G::NL];
-    auto issue_loads = [&](u32x4 (&kreg)[G::NL], u32x4 (&vreg)[G::NL], int t) {
+    // K/V tiles go from global memory straight into LDS (buffer loads with the LDS bit): no staging
+    // registers, no LDS store instructions.  One wave-wide load moves 64 x 16 B = RPW whole rows into 1 KiB
+    // of contiguous LDS; load i of wave w carries rows (i*4 + w)*RPW .. of the tile.  Each tile of K and V
+    // is a raw buffer resource whose 64-bit base is scalar arithmetic (sub-tensors of any size are
+    // addressable); a lane adds one offset that is the same for the whole kernel - its row inside the
+    // load and the chunk it fetches, which is the chunk its LDS position holds under the permutation - and
+    // the load adds a scalar row offset.  num_records ends at the last row of the context: rows past it
+    // fail the hardware range check, touch nothing and put zeros into LDS, so no byte beyond what step()
+    // has mapped is read (their scores are masked, their zero V rows are multiplied by zero weights).
+    const int dma_row = l / G::CH;                                    // row inside one load
+    const int dma_voff = dma_row * rs32 + (((l % G::CH) ^ G::swz((w * G::RPW + dma_row))) << 4);
+    // The loads are written as inline assembly: the compiler does not see them, so its wait-counter pass
+    // does not make the LDS reads of tile t wait for the loads of tile t+1 (it cannot tell the two stages
+    // apart); the waits that are needed are placed by hand before the barriers.  No other vector-memory
+    // instruction is issued between the first of these loads and the end of the loop.
+    auto issue_loads = [&](int t) {
         const int tok = t * kBN;
         const int64_t boff = static_cast<int64_t>(tok) * rs32;
         const int rows = min(kv_len - tok, kBN);   // <= 0 past the end: everything out of range
-        const int nrec = rows > 0 ? (rows - 1) * rs32 + G::RB : 0;
-        const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kp + boff), 0, nrec, kRsrcWord3);
-        const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vp + boff), 0, nrec, kRsrcWord3);
+        const uint32_t nrec = rows > 0 ? static_cast<uint32_t>((rows - 1) * rs32 + G::RB) : 0u;
+        const uint64_t ka = reinterpret_cast<uint64_t>(kp + boff), va = reinterpret_cast<uint64_t>(vp + boff);
+        // raw buffer resource: base[47:0], stride 0, num_records, data format word
+        const u32x4 krs = {static_cast<uint32_t>(ka), static_cast<uint32_t>(ka >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
+        const u32x4 vrs = {static_cast<uint32_t>(va), static_cast<uint32_t>(va >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
+        const uint32_t kb = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + (t & 1) * G::BUF + w * 1024;   // LDS byte address
 #pragma unroll
-        for (int i = 0; i < G::NL; ++i) {
-            const int so = i * G::RPI * rs32;
-            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, lane_off, so, 0);
-            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, lane_off, so, 0);
-        }
-    };
-    auto store_tile = [&](const u32x4 (&kreg)[G::NL], const u32x4 (&vreg)[G::NL], int buf) {
-        char* kb = lds + buf * G::BUF;
-        char* vb = kb + kBN * G::KSTR;
-#pragma unroll
-        for (int i = 0; i < G::NL; ++i) {
-            const int row = i * G::RPI + ld_row;
-            *reinterpret_cast<u32x4*>(kb + row * G::KSTR + ld_col) = kreg[i];
-            *reinterpret_cast<u32x4*>(vb + row * G::VSTR + ld_col) = vreg[i];
+        for (int i = 0; i < G::NLW; ++i) {
+            const int so = (i * 4 + w) * G::RPW * rs32;   // scalar
+            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :: "s"(kb + i * 4096), "v"(dma_voff), "s"(krs), "s"(so) : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :: "s"(kb + G::KV + i * 4096), "v"(dma_voff), "s"(vrs), "s"(so) : "memory", "m0");
         }
     };
 
     const float scale_log2 = a.scale * kLog2e;
-    float m[QB], lsum[QB];
-    f32x16 o[QB][D / 32];
+    float m = -INFINITY, lsum = 0.f;
+    f32x16 o[D / 32];
 #pragma unroll
-    for (int qa = 0; qa < QB; ++qa) {
-        m[qa] = -INFINITY;
-        lsum[qa] = 0.f;
+    for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[qa][db][i] = 0.f;
-    }
+        for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
 
     const int wave_last_key = min(row_lo + WR - 1, q_len - 1) + off;  // last key any row of the wave sees
-    const int vrow = (l >> 5) * 4 + ((l & 15) >> 2);
-    const int vcol = ((l >> 4) & 1) * 32 + (l & 3) * 8;
+    // Per-lane LDS read offsets under the chunk permutation.  K fragment (k-step ks): lane reads row l%32
+    // (+32 for the second token half), logical chunk 2*ks + l/32.  V fragment (channel block db): lane
+    // reads 8 bytes of row vrow (+8, +16, +32), logical 32-byte pair 2*db + (l/16)%2.  In both cases the
+    // row's permutation value depends on the lane only.
+    int koff[D / 16], voff[D / 32];
+    {
+        const int sh = G::swz(l & 31) >> 1;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) koff[ks] = (l & 31) * G::RB + ((ks ^ sh) << 5) + (l >> 5) * 16;
+        const int vrow = (l >> 5) * 4 + ((l & 15) >> 2);
+        const int shv = G::swz(vrow) >> 1;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) voff[db] = vrow * G::RB + (((db * 2 + ((l >> 4) & 1)) ^ shv) << 5) + (l & 3) * 8;
+    }
 
-    // One KV tile in two parts, S^T = K Q^T first, then online softmax and O^T += V^T P^T; the caller
-    // issues the global prefetch between the two (one issue site, whether or not the wave skips a tile
-    // that lies entirely above its diagonal).
-    f32x16 s[QB][2];
+    // One KV tile in two parts, S^T = K Q^T first, then online softmax and O^T += V^T P^T.
+    f32x16 s[2];
     auto wave_active = [&](int t) { return t * kBN <= wave_last_key && row_lo < q_len; };
     auto tile_scores = [&](int t) {
         const char* kb = lds + (t & 1) * G::BUF;
 #pragma unroll
-        for (int qa = 0; qa < QB; ++qa)
+        for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[qa][tb][i] = 0.f;
+            for (int i = 0; i < 16; ++i) s[tb][i] = 0.f;
         // operands are fetched several multiplies ahead so the matrix pipe is not paced by LDS latency;
         // the wave runs at raised priority while it feeds the matrix pipe
         __builtin_amdgcn_s_setprio(1);
@@ -177,72 +180,66 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
         bf16x8 ka[NF];
 #pragma unroll
         for (int f = 0; f < NF; ++f)
-            ka[f] = *reinterpret_cast<const bf16x8*>(kb + ((f & 1) * 32 + (l & 31)) * G::KSTR + (f >> 1) * 32 + (l >> 5) * 16);
+            ka[f] = *reinterpret_cast<const bf16x8*>(kb + (f & 1) * 32 * G::RB + koff[f >> 1]);
 #pragma unroll
         for (int f = 0; f < NF; ++f)
-#pragma unroll
-            for (int qa = 0; qa < QB; ++qa)
-                s[qa][f & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[f], qb[qa][f >> 1], s[qa][f & 1], 0, 0, 0);
+            s[f & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[f], qb[f >> 1], s[f & 1], 0, 0, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
 #pragma unroll
         for (int f = 0; f < NF - 6; ++f) {
-            __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 6 * QB, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
         __builtin_amdgcn_s_setprio(0);
     };
     auto tile_softmax_pv = [&](int t) {
-        const char* vb = lds + (t & 1) * G::BUF + kBN * G::KSTR;
+        const char* vb = lds + (t & 1) * G::BUF + G::KV;
         const int t0 = t * kBN;
-        bf16x8 pb[QB][4];
-#pragma unroll
-        for (int qa = 0; qa < QB; ++qa) {
-            // lane owns query row my_row[qa]; s[qa][tb][i] is token t0 + tb*32 + (i/4)*8 + (l/32)*4 + i%4
-            if (t0 + kBN - 1 > row_lo + qa * 32 + off) {   // tile crosses the diagonal for some row of the block
-                const int limit = my_row[qa] + off;        // last visible key of this lane's row
-                const int tl = t0 + (l >> 5) * 4;
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (tl + tb * 32 + (i >> 2) * 8 + (i & 3) > limit) s[qa][tb][i] = -INFINITY;
-            }
-            float mx = s[qa][0][0];
+        bf16x8 pb[4];
+        // lane owns query row my_row; s[tb][i] is token t0 + tb*32 + (i/4)*8 + (l/32)*4 + i%4
+        if (t0 + kBN - 1 > row_lo + off) {             // tile crosses the diagonal for some row of the wave
+            const int limit = my_row + off;            // last visible key of this lane's row
+            const int tl = t0 + (l >> 5) * 4;
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[qa][tb][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;   // scale > 0: max commutes with scaling
-            // Query rows past q_len hold a copy of the last row's Q, and key 0 is visible to every row, so
-            // the first tile always raises m from -inf to a finite value for all lanes.
-            if (__builtin_amdgcn_ballot_w64(mx > m[qa] + kLazy) != 0) {
-                const float m_new = fmaxf(m[qa], mx);
-                const float alpha = __builtin_amdgcn_exp2f(m[qa] - m_new);
-                m[qa] = m_new;
-                lsum[qa] *= alpha;
-#pragma unroll
-                for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) o[qa][db][i] *= alpha;
-            }
-            const float neg_m = -m[qa];
-            bf16x2 ones;
-            ones[0] = static_cast<__bf16>(1.0f);
-            ones[1] = static_cast<__bf16>(1.0f);
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    bf16x2 pp;
-                    pp[0] = static_cast<__bf16>(__builtin_amdgcn_exp2f(__builtin_fmaf(s[qa][tb][i], scale_log2, neg_m)));
-                    pp[1] = static_cast<__bf16>(__builtin_amdgcn_exp2f(__builtin_fmaf(s[qa][tb][i + 1], scale_log2, neg_m)));
-                    // the row sum is taken over the rounded probabilities, the same values P V uses
-                    lsum[qa] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, lsum[qa], false);
-                    pb[qa][tb * 2 + (i >> 3)][i & 7] = pp[0];
-                    pb[qa][tb * 2 + (i >> 3)][(i & 7) + 1] = pp[1];
-                }
+                for (int i = 0; i < 16; ++i)
+                    if (tl + tb * 32 + (i >> 2) * 8 + (i & 3) > limit) s[tb][i] = -INFINITY;
         }
+        float mx = s[0][0];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[tb][i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;   // scale > 0: max commutes with scaling
+        // Query rows past q_len hold a copy of the last row's Q, and key 0 is visible to every row, so
+        // the first tile always raises m from -inf to a finite value for all lanes.
+        if (__builtin_amdgcn_ballot_w64(mx > m + kLazy) != 0) {
+            const float m_new = fmaxf(m, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            m = m_new;
+            lsum *= alpha;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+        }
+        const float neg_m = -m;
+        float lpart[2] = {0.f, 0.f};
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[tb][i], scale_log2, neg_m));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[tb][i + 1], scale_log2, neg_m));
+                // row sum in fp32 with plain adds (the bf16 dot-product instruction shares hardware with the
+                // matrix pipe and stalls it); two partial sums keep the chains short
+                lpart[tb] += p0 + p1;
+                pb[tb * 2 + (i >> 3)][i & 7] = static_cast<__bf16>(p0);
+                pb[tb * 2 + (i >> 3)][(i & 7) + 1] = static_cast<__bf16>(p1);
+            }
+        lsum += lpart[0] + lpart[1];
 
         // O^T += V^T P^T.  A operand: lane (d = db*32 + l%32, h = l/32), 8 tokens per k-step (kk = tb*2 + s').
         __builtin_amdgcn_s_setprio(1);
@@ -251,64 +248,57 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int f = 0; f < NV; ++f) {
             const int kk = f / (D / 32), db = f % (D / 32);
-            const int trow = (kk >> 1) * 32 + (kk & 1) * 16 + vrow;
-            const char* p0 = vb + trow * G::VSTR + db * 64 + vcol;
+            const char* p0 = vb + ((kk >> 1) * 32 + (kk & 1) * 16) * G::RB + voff[db];
             vlo[f] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
-            vhi[f] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * G::VSTR));
+            vhi[f] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * G::RB));
         }
 #pragma unroll
         for (int f = 0; f < NV; ++f) {
             const int kk = f / (D / 32), db = f % (D / 32);
             const bf16x8 va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(vlo[f], vhi[f], 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-            for (int qa = 0; qa < QB; ++qa)
-                o[qa][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[qa][kk], o[qa][db], 0, 0, 0);
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kk], o[db], 0, 0, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);
 #pragma unroll
         for (int f = 0; f < NV - 6; ++f) {
-            __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 6 * QB, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
         __builtin_amdgcn_s_setprio(0);
     };
 
-    issue_loads(kregA, vregA, 0);
-    store_tile(kregA, vregA, 0);
+    issue_loads(0);
+    // everything requested so far - Q and tile 0 - has landed before the loop starts
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
     __syncthreads();
-    // make sure the Q fragments have landed before the loop, so that no wait for them (which would also
-    // wait for younger K/V prefetches) is left inside it
-#pragma unroll
-    for (int qa = 0; qa < QB; ++qa)
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(qb[qa][ks]));
 
     for (int t = 0; t < ntiles; ++t) {
-        if (wave_active(t)) tile_scores(t);
-        issue_loads(kregA, vregA, t + 1);
-        if (wave_active(t)) tile_softmax_pv(t);
-        store_tile(kregA, vregA, (t + 1) & 1);
+        // tile t+1 goes into the other stage, which every wave finished reading before the last barrier;
+        // a tile index past the end is out of range for every lane and only writes zeros
+        issue_loads(t + 1);
+        if (wave_active(t)) {
+            tile_scores(t);
+            tile_softmax_pv(t);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's part of tile t+1 is in LDS
         __syncthreads();
     }
 
+    lsum += __shfl_xor(lsum, 32);
+    if (my_row < q_len) {
+        const float inv = 1.f / lsum;
+        char* orow = static_cast<char*>(a.o) + ((static_cast<int64_t>(q_begin) + my_row) * a.Hq + head) * G::RB;
 #pragma unroll
-    for (int qa = 0; qa < QB; ++qa) {
-        lsum[qa] += __shfl_xor(lsum[qa], 32);
-        if (my_row[qa] < q_len) {
-            const float inv = 1.f / lsum[qa];
-            char* orow = static_cast<char*>(a.o) + ((static_cast<int64_t>(q_begin) + my_row[qa]) * a.Hq + head) * G::RB;
+        for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db)
+            for (int q4 = 0; q4 < 4; ++q4) {
+                bf16x4 v;
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    bf16x4 v;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = static_cast<__bf16>(o[qa][db][q4 * 4 + e] * inv);
-                    const int d = db * 32 + q4 * 8 + (l >> 5) * 4;
-                    *reinterpret_cast<u32x2*>(orow + d * 2) = __builtin_bit_cast(u32x2, v);
-                }
-        }
+                for (int e = 0; e < 4; ++e) v[e] = static_cast<__bf16>(o[db][q4 * 4 + e] * inv);
+                const int d = db * 32 + q4 * 8 + (l >> 5) * 4;
+                *reinterpret_cast<u32x2*>(orow + d * 2) = __builtin_bit_cast(u32x2, v);
+            }
     }
 }
 
