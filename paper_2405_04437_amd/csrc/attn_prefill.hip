@@ -53,10 +53,13 @@ template <int D> struct PGeo {
     static constexpr int LDS = 2 * BUF;
     // Rows are stored unpadded (the loads below write LDS directly, 1 KiB contiguous per instruction), so
     // bank conflicts are avoided by permuting the 16-byte chunks inside each row instead: chunk c of row r
-    // is stored at chunk position c ^ swz(r).  swz is even (32-byte pairs stay adjacent for the
-    // transposing reads) and takes 8 (D = 128) or 4 (D = 64) different values over any run of rows that
-    // falls on the same banks.
-    __device__ static constexpr int swz(int row) { return (((row * RB / 256) & 7) << 1) & (CH - 1); }
+    // is stored at chunk position c ^ swz(r).  LDS has 64 banks of 4 bytes, i.e. 256 bytes per clock:
+    //  * a K fragment read (16 B per lane) is served 16 lanes at a time - 16 consecutive rows, same logical
+    //    chunk - so the K permutation takes 16 different values over 16 rows' worth of 256 B;
+    //  * a transposing V read (8 B per lane) is served 32 lanes at a time - 4 consecutive rows, 64 B each -
+    //    so the V permutation moves whole 64-byte groups (4 chunks) and differs between those 4 rows.
+    __device__ static constexpr int swz_k(int row) { return (row * RB / 256) & (CH - 1); }
+    __device__ static constexpr int swz_v(int row) { return ((row * RB / 256) & (RB / 64 - 1)) << 2; }
 };
 
 typedef __attribute__((address_space(3))) void* lds_ptr;
@@ -115,7 +118,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
     // fail the hardware range check, touch nothing and put zeros into LDS, so no byte beyond what step()
     // has mapped is read (their scores are masked, their zero V rows are multiplied by zero weights).
     const int dma_row = l / G::CH;                                    // row inside one load
-    const int dma_voff = dma_row * rs32 + (((l % G::CH) ^ G::swz((w * G::RPW + dma_row))) << 4);
+    const int dma_tile_row = w * G::RPW + dma_row;                    // row in the tile, up to a multiple of 4*RPW
+    const int dma_voff_k = dma_row * rs32 + (((l % G::CH) ^ G::swz_k(dma_tile_row)) << 4);
+    const int dma_voff_v = dma_row * rs32 + (((l % G::CH) ^ G::swz_v(dma_tile_row)) << 4);
     // The loads are written as inline assembly: the compiler does not see them, so its wait-counter pass
     // does not make the LDS reads of tile t wait for the loads of tile t+1 (it cannot tell the two stages
     // apart); the waits that are needed are placed by hand before the barriers.  No other vector-memory
@@ -134,9 +139,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
         for (int i = 0; i < G::NLW; ++i) {
             const int so = (i * 4 + w) * G::RPW * rs32;   // scalar
             asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :: "s"(kb + i * 4096), "v"(dma_voff), "s"(krs), "s"(so) : "memory", "m0");
+                         :: "s"(kb + i * 4096), "v"(dma_voff_k), "s"(krs), "s"(so) : "memory", "m0");
             asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :: "s"(kb + G::KV + i * 4096), "v"(dma_voff), "s"(vrs), "s"(so) : "memory", "m0");
+                         :: "s"(kb + G::KV + i * 4096), "v"(dma_voff_v), "s"(vrs), "s"(so) : "memory", "m0");
         }
     };
 
@@ -149,19 +154,19 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
         for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
 
     const int wave_last_key = min(row_lo + WR - 1, q_len - 1) + off;  // last key any row of the wave sees
-    // Per-lane LDS read offsets under the chunk permutation.  K fragment (k-step ks): lane reads row l%32
+    // Per-lane LDS read offsets under the chunk permutations.  K fragment (k-step ks): lane reads row l%32
     // (+32 for the second token half), logical chunk 2*ks + l/32.  V fragment (channel block db): lane
-    // reads 8 bytes of row vrow (+8, +16, +32), logical 32-byte pair 2*db + (l/16)%2.  In both cases the
+    // reads 8 bytes of row vrow (+8, +16, +32) inside the logical 64-byte group db.  In both cases the
     // row's permutation value depends on the lane only.
     int koff[D / 16], voff[D / 32];
     {
-        const int sh = G::swz(l & 31) >> 1;
+        const int sk = G::swz_k(l & 31);
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) koff[ks] = (l & 31) * G::RB + ((ks ^ sh) << 5) + (l >> 5) * 16;
+        for (int ks = 0; ks < D / 16; ++ks) koff[ks] = (l & 31) * G::RB + (((2 * ks + (l >> 5)) ^ sk) << 4);
         const int vrow = (l >> 5) * 4 + ((l & 15) >> 2);
-        const int shv = G::swz(vrow) >> 1;
+        const int sv = G::swz_v(vrow) >> 2;
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db) voff[db] = vrow * G::RB + (((db * 2 + ((l >> 4) & 1)) ^ shv) << 5) + (l & 3) * 8;
+        for (int db = 0; db < D / 32; ++db) voff[db] = vrow * G::RB + ((db ^ sv) << 6) + ((l >> 4) & 1) * 32 + (l & 3) * 8;
     }
 
     // One KV tile in two parts, S^T = K Q^T first, then online softmax and O^T += V^T P^T.
