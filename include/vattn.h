@@ -211,9 +211,10 @@ int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* laun
 int vattn_set_decode_chunk(vattn_ctx* ctx, int tokens);
 int vattn_set_decode_tuning(vattn_ctx* ctx, int segments_per_slot);
 
-/* Selects the prefill kernel: 0 (default) = 128 query rows per workgroup, two workgroups per CU;
- * 1 = 256 rows per workgroup, one per CU, every K/V fragment read from LDS feeds two matrix
- * instructions.  Same results up to floating-point summation order. */
+/* Selects the prefill kernel.  Both take 256 query rows per workgroup, one workgroup per CU:
+ * 0 (default) = eight waves of 32 rows; 1 = four waves of 64 rows, every K/V fragment read from
+ * LDS feeds two matrix instructions, software-pipelined (measured slower).  Same results up to
+ * floating-point summation order. */
 int vattn_set_prefill_wide(vattn_ctx* ctx, int enabled);
 
 const char* vattn_last_error(void);

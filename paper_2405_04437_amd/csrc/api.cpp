@@ -260,7 +260,7 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
     // 128 query rows per work item by default; the wide kernel (256 rows, one workgroup per CU,
     // software-pipelined) is opt-in: measured equal on long prompts and slower on short ones.
     const bool wide = ctx->prefill_wide;
-    const int BM = wide ? 256 : 128;
+    const int BM = wide ? 256 : kPrefillRows;
     for (int r = 0; r < n; ++r) {
         const int64_t ql = static_cast<int64_t>(cu_q[r + 1]) - cu_q[r];
         if (ql < 0) { set_error("attn_prefill: cu_q must be non-decreasing"); return -1; }

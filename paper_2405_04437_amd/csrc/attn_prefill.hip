@@ -5,7 +5,8 @@
 // sub-tensor at base + reqId*S (Sec. 5.2.3): no block table, one pointer and one stride.
 //
 // gfx950 mapping
-//  * One workgroup (4 waves) owns 128 query rows of one query head; each wave owns 32 rows.  KV is
+//  * One workgroup (kPrefillWaves = 8 waves, one workgroup per CU, two waves per SIMD) owns 256 query
+//    rows of one query head, 32 per wave; all eight waves share each K/V tile.  KV is
 //    walked in tiles of 64 tokens, double buffered in LDS; tile t+1 travels from global memory straight
 //    into LDS (buffer loads with the LDS bit) while tile t is being multiplied.
 //  * Both contractions use v_mfma_f32_32x32x16_bf16.  Scores are produced transposed,
@@ -34,7 +35,9 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 constexpr int kBN = 64;    // KV tokens per tile
-constexpr int kThreads = 256;
+constexpr int kAhead = 6;               // matrix operands requested from LDS this many multiplies ahead
+constexpr int kWaves = kPrefillWaves;   // waves per workgroup, 32 query rows each
+constexpr int kThreads = kWaves * 64;
 constexpr float kLog2e = 1.4426950408889634f;
 // The running maximum is only raised when some row's tile maximum exceeds it by more than this many
 // binary orders of magnitude: exponentials then stay below 2^kLazy, which fp32 sums and bf16 P hold
@@ -47,7 +50,8 @@ template <int D> struct PGeo {
     static constexpr int RB = D * 2;                         // bytes per head row
     static constexpr int CH = RB / 16;                       // 16-byte chunks per row
     static constexpr int RPW = 1024 / RB;                    // rows one wave-wide 16 B/lane load covers
-    static constexpr int NLW = kBN / 4 / RPW;                // such loads per wave, per tile and tensor
+    static constexpr int NB = kBN / RPW;                     // such loads per tile and tensor; wave w issues loads w, w+kWaves, ...
+    static constexpr int NLW = (NB + kWaves - 1) / kWaves;   // at most this many per wave
     static constexpr int KV = kBN * RB;                      // one K (or V) tile in LDS, rows unpadded
     static constexpr int BUF = 2 * KV;                       // one K+V stage
     static constexpr int LDS = 2 * BUF;
@@ -67,7 +71,7 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
     using G = PGeo<D>;
-    constexpr int BM = 128;                    // query rows per workgroup
+    constexpr int BM = kPrefillRows;           // query rows per workgroup
     constexpr int WR = 32;                     // query rows per wave
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
@@ -110,7 +114,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
 
     // K/V tiles go from global memory straight into LDS (buffer loads with the LDS bit): no staging
     // registers, no LDS store instructions.  One wave-wide load moves 64 x 16 B = RPW whole rows into 1 KiB
-    // of contiguous LDS; load i of wave w carries rows (i*4 + w)*RPW .. of the tile.  Each tile of K and V
+    // of contiguous LDS; wave w issues loads w, w + kWaves, ... of a tile (load b carries rows b*RPW ..).  Each tile of K and V
     // is a raw buffer resource whose 64-bit base is scalar arithmetic (sub-tensors of any size are
     // addressable); a lane adds one offset that is the same for the whole kernel - its row inside the
     // load and the chunk it fetches, which is the chunk its LDS position holds under the permutation - and
@@ -118,9 +122,17 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
     // fail the hardware range check, touch nothing and put zeros into LDS, so no byte beyond what step()
     // has mapped is read (their scores are masked, their zero V rows are multiplied by zero weights).
     const int dma_row = l / G::CH;                                    // row inside one load
-    const int dma_tile_row = w * G::RPW + dma_row;                    // row in the tile, up to a multiple of 4*RPW
-    const int dma_voff_k = dma_row * rs32 + (((l % G::CH) ^ G::swz_k(dma_tile_row)) << 4);
-    const int dma_voff_v = dma_row * rs32 + (((l % G::CH) ^ G::swz_v(dma_tile_row)) << 4);
+    // The chunk a lane fetches depends on the row's position in the tile: for V only on the row inside the
+    // load, for K on the load's index modulo PB (the K permutation repeats every 16 rows' worth of 256 B).
+    // With kWaves = 6 the loads of one wave alternate between two such positions.
+    constexpr int PB = 16 * 256 / G::RB / G::RPW;                      // loads per K permutation period (4 or 2)
+    constexpr int STEP = (kWaves % PB == 0) ? PB : (kWaves % PB);    // a wave's loads sit at w + multiples of STEP (mod PB)
+    static_assert(PB % STEP == 0 && PB / STEP <= 2, "unsupported number of waves");
+    int dma_voff_k[2];
+#pragma unroll
+    for (int v = 0; v < 2; ++v)
+        dma_voff_k[v] = dma_row * rs32 + (((l % G::CH) ^ G::swz_k((w + v * STEP) * G::RPW + dma_row)) << 4);
+    const int dma_voff_v = dma_row * rs32 + (((l % G::CH) ^ G::swz_v(dma_row)) << 4);
     // The loads are written as inline assembly: the compiler does not see them, so its wait-counter pass
     // does not make the LDS reads of tile t wait for the loads of tile t+1 (it cannot tell the two stages
     // apart); the waits that are needed are placed by hand before the barriers.  No other vector-memory
@@ -134,14 +146,17 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
         // raw buffer resource: base[47:0], stride 0, num_records, data format word
         const u32x4 krs = {static_cast<uint32_t>(ka), static_cast<uint32_t>(ka >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
         const u32x4 vrs = {static_cast<uint32_t>(va), static_cast<uint32_t>(va >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
-        const uint32_t kb = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + (t & 1) * G::BUF + w * 1024;   // LDS byte address
+        const uint32_t kb = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + (t & 1) * G::BUF;   // LDS byte address
 #pragma unroll
-        for (int i = 0; i < G::NLW; ++i) {
-            const int so = (i * 4 + w) * G::RPW * rs32;   // scalar
-            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :: "s"(kb + i * 4096), "v"(dma_voff_k), "s"(krs), "s"(so) : "memory", "m0");
-            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :: "s"(kb + G::KV + i * 4096), "v"(dma_voff_v), "s"(vrs), "s"(so) : "memory", "m0");
+        for (int j = 0; j < G::NLW; ++j) {
+            const int b = w + j * kWaves;                 // scalar: which 1 KiB block of the tile
+            if (b < G::NB) {
+                const int so = b * G::RPW * rs32;
+                asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                             :: "s"(kb + b * 1024), "v"(dma_voff_k[((j * kWaves) % PB) / STEP]), "s"(krs), "s"(so) : "memory", "m0");
+                asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                             :: "s"(kb + G::KV + b * 1024), "v"(dma_voff_v), "s"(vrs), "s"(so) : "memory", "m0");
+            }
         }
     };
 
@@ -189,13 +204,13 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int f = 0; f < NF; ++f)
             s[f & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[f], qb[f >> 1], s[f & 1], 0, 0, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
 #pragma unroll
-        for (int f = 0; f < NF - 6; ++f) {
+        for (int f = 0; f < NF - kAhead; ++f) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
         __builtin_amdgcn_s_setprio(0);
     };
     auto tile_softmax_pv = [&](int t) {
@@ -263,13 +278,13 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
             const bf16x8 va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(vlo[f], vhi[f], 0, 1, 2, 3, 4, 5, 6, 7));
             o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kk], o[db], 0, 0, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);
 #pragma unroll
-        for (int f = 0; f < NV - 6; ++f) {
+        for (int f = 0; f < NV - kAhead; ++f) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
         __builtin_amdgcn_s_setprio(0);
     };
 

@@ -106,8 +106,12 @@ struct PrefillArgs {
     int items_per_xcd; int n;
     float scale;
 };
-// Two kernels: 128 query rows per work item (two workgroups per CU), and a wide one with 256 rows per
-// work item for long prompts (one workgroup per CU, software-pipelined).
+// Two kernels: the default with kPrefillWaves waves x 32 query rows per work item, and a wide one with
+// 4 waves x 64 rows (software-pipelined).  Both take 256 rows per work item, one workgroup per CU.
+// Measured on C3 / C5 for the default: 8 waves 1.12 / 1.17 PFLOP/s; 4 waves (two workgroups per CU)
+// 1.07 / 1.12; 6 waves at three waves per SIMD (fewer registers, shallower operand prefetch) 0.97 / 1.00.
+constexpr int kPrefillWaves = 8;
+constexpr int kPrefillRows = kPrefillWaves * 32;
 bool launch_prefill(const PrefillArgs& a, hipStream_t stream, LaunchEvents ev = {});
 bool launch_prefill_wide(const PrefillArgs& a, hipStream_t stream, LaunchEvents ev = {});
 
