@@ -1,7 +1,7 @@
 """GPU parity at the full sizes of benchmark configs 3, 4 and 5, in the launch configuration bench.py
 times.  A full CPU oracle is infeasible there (27-140 TFLOP), so outputs are checked on seeded samples
 of query rows / requests that the oracle computes one by one: always the first and last row, rows next
-to query-tile, KV-tile and page-group boundaries, and uniformly drawn rows.  Inputs are drawn on the
+to query-tile, KV-tile and page-group boundaries, and uniformly drawn rows - 512 rows per config, every head of each.  Inputs are drawn on the
 device from a seeded generator and copied back for the sampled requests only."""
 import numpy as np
 import pytest
@@ -44,7 +44,7 @@ def _randn_bf16(torch, gen, shape):
 
 def _boundaries(q_len, off, shape):
     page_tokens = 2 * MiB // shape.token_bytes
-    b = [128, 256, 64 - off % 64, 2 * page_tokens - off, page_tokens - off, q_len - 256, q_len - 128, q_len - 64]
+    b = [128, 256, 512, q_len - 512, 64 - off % 64, 2 * page_tokens - off, page_tokens - off, q_len - 256, q_len - 128, q_len - 64]
     return [x for x in b if 0 < x < q_len]
 
 
@@ -67,7 +67,7 @@ def test_config3_llama3_8b_prefill_sampled_rows():
         outs[wide] = sess.prefill(0, q, ids, cu, wl.kv_lens, scale)
     torch.cuda.synchronize()
     for r in range(wl.n):
-        rows = W.sample_rows(wl.q_lens[r], 24, seed=wl.seed + r, boundaries=_boundaries(wl.q_lens[r], 0, shape))
+        rows = W.sample_rows(wl.q_lens[r], 64, seed=wl.seed + r, boundaries=_boundaries(wl.q_lens[r], 0, shape))
         qb = tensor_to_bits(q[int(cu[r]):int(cu[r + 1])])
         want = OA.attention_request(qb, kv[r][0], kv[r][1], scale, rows=rows)
         for wide in (False, True):
@@ -133,7 +133,7 @@ def test_config4_yi34b_mixed_step_with_churn():
         check(od_f[slot:slot + 1], want, f"C4 decode slot {slot} (ctx {lens1[slot]})")
     k = np.concatenate([chunk_kv[0], tensor_to_bits(ck)])
     v = np.concatenate([chunk_kv[1], tensor_to_bits(cv)])
-    rows = W.sample_rows(2048, 40, seed=wl.seed, boundaries=_boundaries(2048, 8192, shape))
+    rows = W.sample_rows(2048, 512, seed=wl.seed, boundaries=_boundaries(2048, 8192, shape))
     want = OA.attention_request(tensor_to_bits(qc), k, v, scale, rows=rows)
     check(tensor_to_f32(oc)[rows], want, "C4 prefill chunk appended at 8192")
     sess.close()
@@ -152,7 +152,7 @@ def test_config5_long_context_prefill_then_decode():
     sess.step()
     k_b, v_b = _fill(sess, torch, gen, shape, rid, L, keep=True)
     q = torch.cat([_randn_bf16(torch, gen, (16384, shape.num_q_heads, shape.head_dim)) for _ in range(L // 16384)])
-    rows = W.sample_rows(L, 20, seed=wl.seed, boundaries=_boundaries(L, 0, shape) + [L // 2])
+    rows = W.sample_rows(L, 512, seed=wl.seed, boundaries=_boundaries(L, 0, shape) + [L // 2])
     qb_rows = tensor_to_bits(q[torch.from_numpy(rows.astype(np.int64)).cuda()])
     # the oracle takes the request's own query rows: evaluate each sampled row as a one-row chunk whose
     # context ends at that row (the same causal definition, without materialising all of Q on the host)
