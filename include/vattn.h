@@ -192,6 +192,19 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q /*d
                       void* o /*device*/, const int32_t* reqids /*host*/, const int64_t* kv_lens /*host*/,
                       int n, float scale, void* workspace /*device*/, size_t workspace_bytes);
 
+/* Comparison kernel, not part of the method: the SAME split-K decode over a PAGED KV cache, the design
+ * the paper argues against (Sec. 3: block table inside the kernel), to re-measure on this GPU what the
+ * indirection costs.  k_pool, v_pool: caller-owned device pools [num_blocks, block_tokens, H, D] bf16;
+ * block_table [n, max_blocks_per_req] (HOST; validated and uploaded): entry j of row r names the block
+ * that holds tokens j*block_tokens .. of batch slot r.  block_tokens: a multiple of 32.  The context
+ * only supplies the head geometry; its own KV buffers are not touched.  Same workspace rule as
+ * vattn_attn_decode (vattn_decode_workspace_bytes with the same kv_lens). */
+int vattn_attn_decode_paged(vattn_ctx* ctx, void* stream, const void* q /*device*/, void* o /*device*/,
+                            const void* k_pool /*device*/, const void* v_pool /*device*/, int64_t num_blocks,
+                            int block_tokens, const int32_t* block_table /*host*/, int max_blocks_per_req,
+                            const int64_t* kv_lens /*host*/, int n, float scale, void* workspace /*device*/,
+                            size_t workspace_bytes);
+
 /* ---- measurement helpers --------------------------------------------------------------------- */
 
 /* When enabled, every launch of the split-K decode kernel, the reduce kernel and the prefill kernel

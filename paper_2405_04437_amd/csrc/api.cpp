@@ -195,21 +195,25 @@ int64_t vattn_decode_workspace_bytes(vattn_ctx* ctx, const int64_t* kv_lens, int
     return static_cast<int64_t>(decode_workspace_need(ctx, p, n));
 }
 
-int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
-                      const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes) {
-    if (!check_ctx_layer(ctx, layer, "attn_decode")) return -1;
-    if (n < 0 || (n > 0 && (!q || !o || !reqids || !kv_lens || !workspace))) { set_error("attn_decode: null argument"); return -1; }
-    if (n == 0) return 0;
-    for (int r = 0; r < n; ++r) {
-        if (kv_lens[r] < 1) { set_error("attn_decode: context length must be >= 1"); return -1; }
-        if (!check_request(ctx, reqids[r], kv_lens[r], "attn_decode")) return -1;
-    }
+}  // extern "C"
+
+namespace {
+
+// Paged comparison variant: pools and block table instead of the context's virtual buffers.
+struct PagedKv { const void* k_pool; const void* v_pool; int64_t num_blocks; int block_tokens; const int32_t* table; int table_stride; };
+
+// Shared by vattn_attn_decode and vattn_attn_decode_paged: split-K plan, index upload, the two launches.
+int decode_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
+                  const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes, const PagedKv* paged,
+                  const char* fn) {
     const DecodePlan plan = plan_decode(ctx, kv_lens, n);
-    if (plan.total_tiles > INT32_MAX) { set_error("attn_decode: batch too large"); return -1; }
-    const bool inl = n <= kInlineMaxReq;
+    if (plan.total_tiles > INT32_MAX) { set_error(std::string(fn) + ": batch too large"); return -1; }
+    const bool inl = n <= kInlineMaxReq && !paged;
     InlineMeta im;
     const size_t off_kv = sizeof(int32_t) * n, off_cu = off_kv * 2;
-    const size_t bytes = off_cu + sizeof(int32_t) * (n + 1);
+    const size_t off_tab = align_up(off_cu + sizeof(int32_t) * (n + 1), 16);
+    const size_t tab_bytes = paged ? sizeof(int32_t) * static_cast<size_t>(n) * paged->table_stride : 0;
+    const size_t bytes = paged ? off_tab + tab_bytes : off_cu + sizeof(int32_t) * (n + 1);
     char *h = nullptr, *d = nullptr;
     if (!inl && !ctx->ring.acquire(bytes, &h, &d)) return -1;
     int32_t* h_req = inl ? im.v : reinterpret_cast<int32_t*>(h);
@@ -217,24 +221,32 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, vo
     int32_t* h_cu = inl ? im.v + 2 * n : reinterpret_cast<int32_t*>(h + off_cu);
     int64_t total = 0;
     for (int r = 0; r < n; ++r) {
-        h_req[r] = reqids[r];
+        h_req[r] = reqids ? reqids[r] : 0;
         h_kv[r] = static_cast<int32_t>(kv_lens[r]);
         h_cu[r] = static_cast<int32_t>(total);
         total += (kv_lens[r] + 31) / 32;
     }
     h_cu[n] = static_cast<int32_t>(total);
+    if (paged) std::memcpy(h + off_tab, paged->table, tab_bytes);
     const int Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
     const size_t part_o_bytes = decode_part_o_bytes(ctx, plan, n);
     const size_t need = decode_workspace_need(ctx, plan, n);
-    if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) { set_error("attn_decode: workspace must be 256-byte aligned"); return -1; }
-    if (workspace_bytes < need) { set_error("attn_decode: workspace too small (" + std::to_string(workspace_bytes) + " < " + std::to_string(need) + ")"); return -1; }
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) { set_error(std::string(fn) + ": workspace must be 256-byte aligned"); return -1; }
+    if (workspace_bytes < need) { set_error(std::string(fn) + ": workspace too small (" + std::to_string(workspace_bytes) + " < " + std::to_string(need) + ")"); return -1; }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!inl && !ctx->ring.commit(bytes, s)) return -1;
 
     DecodeArgs a{};
     a.q = q; a.o = o;
-    a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1); a.S = ctx->mem.S();
-    a.Hq = Hq; a.H = ctx->cfg.num_kv_heads; a.D = D; a.row_stride = static_cast<int>(ctx->mem.token_stride());
+    if (paged) {
+        a.k_base = static_cast<const char*>(paged->k_pool); a.v_base = static_cast<const char*>(paged->v_pool); a.S = 0;
+        a.row_stride = static_cast<int>(ctx->mem.T());
+        a.block_table = reinterpret_cast<const int32_t*>(d + off_tab); a.table_stride = paged->table_stride; a.block_tokens = paged->block_tokens;
+    } else {
+        a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1); a.S = ctx->mem.S();
+        a.row_stride = static_cast<int>(ctx->mem.token_stride());
+    }
+    a.Hq = Hq; a.H = ctx->cfg.num_kv_heads; a.D = D;
     a.inline_meta = inl ? 1 : 0;
     a.reqids = reinterpret_cast<const int32_t*>(d);
     a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
@@ -248,6 +260,45 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, vo
     if (!launch_decode_splitk(a, imp, s, ev_split)) return -1;
     if (!launch_decode_reduce(a, imp, s, ev_reduce)) return -1;
     return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
+                      const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes) {
+    if (!check_ctx_layer(ctx, layer, "attn_decode")) return -1;
+    if (n < 0 || (n > 0 && (!q || !o || !reqids || !kv_lens || !workspace))) { set_error("attn_decode: null argument"); return -1; }
+    if (n == 0) return 0;
+    for (int r = 0; r < n; ++r) {
+        if (kv_lens[r] < 1) { set_error("attn_decode: context length must be >= 1"); return -1; }
+        if (!check_request(ctx, reqids[r], kv_lens[r], "attn_decode")) return -1;
+    }
+    return decode_common(ctx, layer, stream, q, o, reqids, kv_lens, n, scale, workspace, workspace_bytes, nullptr, "attn_decode");
+}
+
+int vattn_attn_decode_paged(vattn_ctx* ctx, void* stream, const void* q, void* o, const void* k_pool, const void* v_pool,
+                            int64_t num_blocks, int block_tokens, const int32_t* block_table, int max_blocks_per_req,
+                            const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes) {
+    if (!ctx) { set_error("attn_decode_paged: null context"); return -1; }
+    if (n < 0 || (n > 0 && (!q || !o || !k_pool || !v_pool || !block_table || !kv_lens || !workspace))) { set_error("attn_decode_paged: null argument"); return -1; }
+    if (n == 0) return 0;
+    if (block_tokens < 32 || block_tokens % 32 != 0) { set_error("attn_decode_paged: block_tokens must be a positive multiple of 32"); return -1; }
+    if (num_blocks <= 0 || num_blocks > INT32_MAX || max_blocks_per_req <= 0) { set_error("attn_decode_paged: invalid pool or table size"); return -1; }
+    for (int r = 0; r < n; ++r) {
+        if (kv_lens[r] < 1 || kv_lens[r] > static_cast<int64_t>(max_blocks_per_req) * block_tokens) {
+            set_error("attn_decode_paged: context length of slot " + std::to_string(r) + " does not fit its block-table row");
+            return -1;
+        }
+        const int64_t used = (kv_lens[r] + block_tokens - 1) / block_tokens;
+        for (int64_t j = 0; j < used; ++j) {
+            const int32_t b = block_table[static_cast<int64_t>(r) * max_blocks_per_req + j];
+            if (b < 0 || b >= num_blocks) { set_error("attn_decode_paged: block index out of range in slot " + std::to_string(r)); return -1; }
+        }
+    }
+    const PagedKv pk{k_pool, v_pool, num_blocks, block_tokens, block_table, max_blocks_per_req};
+    return decode_common(ctx, 0, stream, q, o, nullptr, kv_lens, n, scale, workspace, workspace_bytes, &pk, "attn_decode_paged");
 }
 
 int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,

@@ -59,7 +59,8 @@ __device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __
 
 // INL: the index arrays are read from the kernel-argument segment (InlineMeta) instead of global memory;
 // a compile-time switch so that both variants keep these uniform reads on the scalar unit.
-template <int D, bool INL>
+// PAGED: the comparison variant - K/V tiles are found through a block table instead of one pointer per request.
+template <int D, bool INL, bool PAGED>
 __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArgs a, int units, int hb_per_kv, InlineMeta im) {
     using G = Geo<D>;
     auto reqid_of = [&](int r) { if constexpr (INL) return im.v[r]; else return a.reqids[r]; };
@@ -100,7 +101,8 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
     const int kv_len = kvlen_of(req);
     const int tok0 = (g0 - r_first) * kTile;
     const int tok1 = min((g1 - r_first) * kTile, kv_len);
-    const int64_t sub = static_cast<int64_t>(reqid_of(req)) * a.S + static_cast<int64_t>(kvh) * G::RB;
+    // contiguous KV: one base per request (Sec. 5.2.3); paged: only the head offset, the block comes per tile
+    const int64_t sub = (PAGED ? 0 : static_cast<int64_t>(reqid_of(req)) * a.S) + static_cast<int64_t>(kvh) * G::RB;
     const char* kp = a.k_base + sub;
     const char* vp = a.v_base + sub;
 
@@ -129,7 +131,13 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
     // byte beyond what step() has mapped is read; their scores are masked below.
     auto issue_loads = [&](u32x4 (&kreg)[G::NL], u32x4 (&vreg)[G::NL], int t) {
         const int tok = tok0 + t * kTile;
-        const int64_t boff = static_cast<int64_t>(tok) * row_stride;
+        int64_t boff;
+        if constexpr (PAGED) {   // block-table lookup: a tile never straddles a block (block_tokens is a multiple of the tile)
+            const int blk = a.block_table[static_cast<int64_t>(req) * a.table_stride + tok / a.block_tokens];
+            boff = (static_cast<int64_t>(blk) * a.block_tokens + tok % a.block_tokens) * row_stride;
+        } else {
+            boff = static_cast<int64_t>(tok) * row_stride;
+        }
         const int nrec = (min(kv_len - tok, kTile) - 1) * row_stride + G::RB;
         const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kp + boff), 0, nrec, kRsrcWord3);
         const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vp + boff), 0, nrec, kRsrcWord3);
@@ -336,7 +344,7 @@ bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t
     const int waves = waves_per_workgroup(a.Hq, a.H);
     dim3 grid(static_cast<unsigned>(a.num_segs), static_cast<unsigned>((units + waves - 1) / waves));
     dim3 block(static_cast<unsigned>(waves * 64));
-    static bool allowed[4] = {false, false, false, false};  // per kernel variant
+    static bool allowed[8] = {};  // per kernel variant
     auto launch = [&](auto kernel, size_t wave_lds, int variant) -> bool {
         // dynamic LDS above 64 KiB has to be allowed once per kernel
         if (!allowed[variant]) {
@@ -347,8 +355,13 @@ bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t
         return true;
     };
     bool ok;
-    if (a.D == 128) ok = a.inline_meta ? launch(decode_splitk_kernel<128, true>, Geo<128>::WAVE_LDS, 0) : launch(decode_splitk_kernel<128, false>, Geo<128>::WAVE_LDS, 1);
-    else ok = a.inline_meta ? launch(decode_splitk_kernel<64, true>, Geo<64>::WAVE_LDS, 2) : launch(decode_splitk_kernel<64, false>, Geo<64>::WAVE_LDS, 3);
+    if (a.block_table) {
+        if (a.D == 128) ok = a.inline_meta ? launch(decode_splitk_kernel<128, true, true>, Geo<128>::WAVE_LDS, 4) : launch(decode_splitk_kernel<128, false, true>, Geo<128>::WAVE_LDS, 5);
+        else ok = a.inline_meta ? launch(decode_splitk_kernel<64, true, true>, Geo<64>::WAVE_LDS, 6) : launch(decode_splitk_kernel<64, false, true>, Geo<64>::WAVE_LDS, 7);
+    } else {
+        if (a.D == 128) ok = a.inline_meta ? launch(decode_splitk_kernel<128, true, false>, Geo<128>::WAVE_LDS, 0) : launch(decode_splitk_kernel<128, false, false>, Geo<128>::WAVE_LDS, 1);
+        else ok = a.inline_meta ? launch(decode_splitk_kernel<64, true, false>, Geo<64>::WAVE_LDS, 2) : launch(decode_splitk_kernel<64, false, false>, Geo<64>::WAVE_LDS, 3);
+    }
     if (!ok) return false;
     return hip_ok(hipGetLastError(), "decode split-K launch");
 }

@@ -90,9 +90,12 @@ struct DecodeArgs {
     float* part_o;   // [num_segs + n, Hq, D] un-normalised partial outputs
     float* part_ml;  // [num_segs + n, Hq, 2] running max (log2 domain) and partial sum
     int inline_meta; // 1: arrays are in InlineMeta as [reqids | kv_lens | cu_tiles]
+    // Paged comparison variant only: k_base / v_base are block pools [num_blocks, block_tokens, H, D] and
+    // block_table[req * table_stride + j] names the block holding tokens j*block_tokens .. of batch slot req.
+    const int32_t* block_table; int table_stride; int block_tokens;
 };
 int decode_resident_workgroups(int Hq, int H, int D, int num_cus);  // workgroups one launch keeps resident
-bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});
+bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});   // paged if a.block_table
 bool launch_decode_reduce(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});
 
 struct PrefillItem { int32_t req; int32_t kvh; int32_t q_tile; int32_t pad; };

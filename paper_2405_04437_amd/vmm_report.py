@@ -10,7 +10,8 @@
      step() mapping synchronously vs the background thread mapping one step ahead (per-iteration step()
      time, its maximum, and where the map calls happened);
   4. deferred reclamation + eager allocation: time from "request arrives" to "prefill may start"
-     (alloc_reqid + step) with pages unmapped on free, deferred, and deferred + eager.
+     (alloc_reqid + step) with pages unmapped on free, deferred, and deferred + eager;
+  5. the decode kernel over contiguous KV vs its paged comparison variant (block table inside the kernel).
 
 Everything runs through the C ABI (paper_2405_04437_amd.binding); no result is checked here - parity lives in
 tests/.  Usage: python paper_2405_04437_amd/vmm_report.py [--quick]
@@ -100,6 +101,51 @@ def page_size_effect(P, torch, W, quick):
         nbytes = n * ctx * 2 * shape.token_bytes
         print(f"| {name} | {us:.1f} | {nbytes / us / 1e3:.0f} |")
         s.close()
+    print()
+
+
+def paged_overhead(P, torch, W, quick):
+    print("## 5. Paged vs contiguous KV in the same decode kernel (Yi-6B shape, 32 requests x 8192 tokens)\n")
+    print("The paged variant looks every 32-token tile up in a block table (blocks scattered over a shuffled pool);")
+    print("the contiguous one adds the tile offset to the request's base pointer.\n")
+    print("| KV layout | split-K kernel us | GB/s |")
+    print("|---|---|---|")
+    shape = W.YI_6B
+    n, ctx = 32, 8192
+    s, ids, shape, gen = _decode_session(P, torch, W, 2 * MiB, 0, n=n, ctx=ctx, layers=1)
+    q = torch.randn((n, shape.num_q_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    o = torch.empty_like(q)
+    lens = [ctx] * n
+    ws = s.workspace(lens)
+    scale = W.softmax_scale(shape.head_dim)
+    nbytes = n * ctx * 2 * shape.token_bytes
+
+    def timed(fn):
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+        s.va.set_timing(True); s.va.kernel_time(0)
+        for _ in range(100):
+            fn()
+        torch.cuda.synchronize()
+        ms, cnt = s.va.kernel_time(0)
+        s.va.set_timing(False)
+        return ms * 1e3 / cnt
+
+    us = timed(lambda: s.decode(0, q, ids, lens, scale, out=o, ws=ws))
+    print(f"| contiguous (virtual tensor) | {us:.1f} | {nbytes / us / 1e3:.0f} |")
+    rng = np.random.default_rng(3)
+    for bt in (32, 64, 256, 2048):
+        per = ctx // bt
+        nb = n * per
+        pool_k = torch.randn((nb, bt, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+        pool_v = torch.randn((nb, bt, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+        table = rng.permutation(nb).astype(np.int32).reshape(n, per)
+        stream = s.stream
+        us = timed(lambda: s.va.attn_decode_paged(stream, q, o, pool_k, pool_v, nb, bt, table, lens, scale, ws, ws.numel()))
+        print(f"| paged, {bt}-token blocks | {us:.1f} | {nbytes / us / 1e3:.0f} |")
+        del pool_k, pool_v
+    s.close()
     print()
 
 
@@ -216,6 +262,7 @@ def main() -> int:
     page_size_effect(P, torch, W, args.quick)
     latency_hiding(P, torch, W, args.quick)
     prefill_admission(P, torch, W, args.quick)
+    paged_overhead(P, torch, W, args.quick)
     return 0
 
 

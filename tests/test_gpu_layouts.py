@@ -138,3 +138,51 @@ def test_sub_tensor_beyond_4gib_is_addressed_correctly():
     od = s.decode(layer, q[ql - 1:ql], [rid], [L], scale)
     check(tensor_to_f32(od), want[-1:], "decode beyond 4 GiB")   # sample_rows always includes the last row
     s.close()
+
+
+@pytest.mark.parametrize("block_tokens", [32, 64, 256])
+@pytest.mark.parametrize("Hq,H,D", [(32, 4, 128), (14, 2, 64)])
+def test_paged_comparison_kernel_matches_oracle(block_tokens, Hq, H, D):
+    """The paged variant of the decode kernel (block table inside the kernel, for measuring what the paper's
+    design avoids) computes the same attention: K/V scattered over a shuffled block pool."""
+    import torch
+    import paper_2405_04437_amd as P
+    from paper_2405_04437_amd.runtime import KvSession, bits_to_tensor, tensor_to_f32
+
+    shape = W.Shape("t", Hq, H, D, 1)
+    kv_lens = [1, 31, 32, 33, 700, 2049, 1300]
+    n = len(kv_lens)
+    inp = W.draw_attention_inputs(shape, [1] * n, kv_lens, seed=block_tokens + D)
+    scale = W.softmax_scale(D)
+    blocks_per = [(L + block_tokens - 1) // block_tokens for L in kv_lens]
+    max_blocks = max(blocks_per)
+    num_blocks = sum(blocks_per) + 5
+    rng = np.random.default_rng(7)
+    ids = rng.permutation(num_blocks)
+    table = np.full((n, max_blocks), -1, dtype=np.int32)   # unused entries stay invalid on purpose
+    kpool = np.zeros((num_blocks, block_tokens, H, D), dtype=np.uint16)
+    vpool = np.zeros_like(kpool)
+    nxt = 0
+    for r, L in enumerate(kv_lens):
+        for j in range(blocks_per[r]):
+            b = int(ids[nxt]); nxt += 1
+            table[r, j] = b
+            a, e = j * block_tokens, min(L, (j + 1) * block_tokens)
+            kpool[b, :e - a] = inp.k[r][a:e]
+            vpool[b, :e - a] = inp.v[r][a:e]
+    s = KvSession(Hq, H, D, 2, 64, 0, 1, 2 * MiB)          # geometry only: no KV memory of its own is used
+    q = bits_to_tensor(inp.q)
+    o = torch.empty_like(q)
+    kp, vp = bits_to_tensor(kpool), bits_to_tensor(vpool)
+    ws = s.workspace(kv_lens)
+    rc = s.va.attn_decode_paged(s.stream, q, o, kp, vp, num_blocks, block_tokens, table, kv_lens, scale, ws, ws.numel())
+    assert rc == 0, P.last_error()
+    want = OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale)
+    check(tensor_to_f32(o), want, f"paged decode block={block_tokens}")
+    # rejected on the host: a used table entry outside the pool, a context longer than its table row, a bad block size
+    bad = table.copy(); bad[4, 1] = num_blocks
+    assert s.va.attn_decode_paged(s.stream, q, o, kp, vp, num_blocks, block_tokens, bad, kv_lens, scale, ws, ws.numel()) == -1
+    long = list(kv_lens); long[0] = max_blocks * block_tokens + 1
+    assert s.va.attn_decode_paged(s.stream, q, o, kp, vp, num_blocks, block_tokens, table, long, scale, ws, ws.numel()) == -1
+    assert s.va.attn_decode_paged(s.stream, q, o, kp, vp, num_blocks, 48, table, kv_lens, scale, ws, ws.numel()) == -1
+    s.close()
