@@ -3,7 +3,8 @@
 
 Headline workload (N=1): BASELINE config 2, "Yi-6B-shaped decode" - 64 requests, 32 query heads,
 4 KV heads, head_dim 128, bf16, contexts U[1024,16384]; every step each request grows by one token:
-    step()  ->  append_kv (new K/V rows, all layers)  ->  attn_decode (split-K + reduce) on one layer
+    step()  ->  append_kv (new K/V rows, all layers; fused into the decode kernel for the attended layer)
+            ->  attn_decode (split-K + reduce) on one layer
 i.e. one pass over all rows of the hot path.  Layers are rotated so consecutive steps read different
 KV buffers.  `value` is algorithmic KV bytes moved per second over the whole step (inputs resident in
 HBM); `roofline` prices the dominant kernel (split-K decode) alone, timed with HIP events the library
@@ -130,10 +131,12 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
                     assert va.append_kv(layer, stream, kbig[:L], vbig[:L], ids[slot:slot + 1], [0, L], [0]) == 0
         seq[ids] = lens + 1
         assert va.step(seq) == 0
+        att = i % layers                  # the layer attended to in this step; its append rides in the decode kernel
         for layer in range(layers):
-            assert va.append_kv(layer, stream, knew, vnew, ids, cu, lens) == 0
+            if layer != att:
+                assert va.append_kv(layer, stream, knew, vnew, ids, cu, lens) == 0
         lens[:] += 1
-        assert va.attn_decode(i % layers, stream, q, o, ids, lens, scale, ws, ws.numel()) == 0
+        assert va.attn_decode_append(att, stream, q, knew, vnew, o, ids, lens, scale, ws, ws.numel()) == 0
         # iteration boundary of the serving loop (Algorithm 1): the framework needs this iteration's
         # output on the host before it can schedule the next one
         torch_stream.synchronize()
@@ -294,7 +297,7 @@ def main() -> int:
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "C2 Yi-6B-shaped decode: 64 requests, Hq=32 H=4 D=128, ctx U[1024,16384], "
-                                  "one token per request per step (step + append_kv + split-K decode + reduce), 2 MiB page-groups"}}
+                                  "one token per request per step (step + append_kv on both layers, fused into the decode kernel for the attended one, + split-K decode + reduce), 2 MiB page-groups"}}
     also = {}
     if args.only == "copy":
         # Calibration for the HBM-traffic counters: a plain device copy of known size (1 GiB read + 1 GiB

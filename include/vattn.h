@@ -192,6 +192,16 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q /*d
                       void* o /*device*/, const int32_t* reqids /*host*/, const int64_t* kv_lens /*host*/,
                       int n, float scale, void* workspace /*device*/, size_t workspace_bytes);
 
+/* Decode attention with the KV append fused in (the "kvcache append inside the attention kernel" of
+ * Sec. 7.1): k_new, v_new [n, H, D] bf16 (device) are the K/V rows of each request's NEWEST token;
+ * kv_lens[r] counts that token (it is position kv_lens[r]-1, which step() must already have mapped).
+ * The kernel stores the rows into the cache of `layer` and attends over all kv_lens[r] tokens; the
+ * result equals vattn_append_kv followed by vattn_attn_decode.  A reqId may appear only once. */
+int vattn_attn_decode_append(vattn_ctx* ctx, int layer, void* stream, const void* q /*device*/,
+                             const void* k_new /*device*/, const void* v_new /*device*/, void* o /*device*/,
+                             const int32_t* reqids /*host*/, const int64_t* kv_lens /*host*/, int n, float scale,
+                             void* workspace /*device*/, size_t workspace_bytes);
+
 /* Comparison kernel, not part of the method: the SAME split-K decode over a PAGED KV cache, the design
  * the paper argues against (Sec. 3: block table inside the kernel), to re-measure on this GPU what the
  * indirection costs.  k_pool, v_pool: caller-owned device pools [num_blocks, block_tokens, H, D] bf16;

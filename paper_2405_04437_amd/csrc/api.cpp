@@ -201,11 +201,12 @@ namespace {
 
 // Paged comparison variant: pools and block table instead of the context's virtual buffers.
 struct PagedKv { const void* k_pool; const void* v_pool; int64_t num_blocks; int block_tokens; const int32_t* table; int table_stride; };
+struct NewRows { const void* k_new; const void* v_new; };
 
 // Shared by vattn_attn_decode and vattn_attn_decode_paged: split-K plan, index upload, the two launches.
 int decode_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
                   const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes, const PagedKv* paged,
-                  const char* fn) {
+                  const NewRows* fresh, const char* fn) {
     const DecodePlan plan = plan_decode(ctx, kv_lens, n);
     if (plan.total_tiles > INT32_MAX) { set_error(std::string(fn) + ": batch too large"); return -1; }
     const bool inl = n <= kInlineMaxReq && !paged;
@@ -247,6 +248,7 @@ int decode_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* 
         a.row_stride = static_cast<int>(ctx->mem.token_stride());
     }
     a.Hq = Hq; a.H = ctx->cfg.num_kv_heads; a.D = D;
+    if (fresh) { a.k_new = fresh->k_new; a.v_new = fresh->v_new; }
     a.inline_meta = inl ? 1 : 0;
     a.reqids = reinterpret_cast<const int32_t*>(d);
     a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
@@ -275,7 +277,22 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, vo
         if (kv_lens[r] < 1) { set_error("attn_decode: context length must be >= 1"); return -1; }
         if (!check_request(ctx, reqids[r], kv_lens[r], "attn_decode")) return -1;
     }
-    return decode_common(ctx, layer, stream, q, o, reqids, kv_lens, n, scale, workspace, workspace_bytes, nullptr, "attn_decode");
+    return decode_common(ctx, layer, stream, q, o, reqids, kv_lens, n, scale, workspace, workspace_bytes, nullptr, nullptr, "attn_decode");
+}
+
+int vattn_attn_decode_append(vattn_ctx* ctx, int layer, void* stream, const void* q, const void* k_new, const void* v_new, void* o,
+                             const int32_t* reqids, const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes) {
+    if (!check_ctx_layer(ctx, layer, "attn_decode_append")) return -1;
+    if (n < 0 || (n > 0 && (!q || !k_new || !v_new || !o || !reqids || !kv_lens || !workspace))) { set_error("attn_decode_append: null argument"); return -1; }
+    if (n == 0) return 0;
+    for (int r = 0; r < n; ++r) {
+        if (kv_lens[r] < 1) { set_error("attn_decode_append: context length must be >= 1"); return -1; }
+        if (!check_request(ctx, reqids[r], kv_lens[r], "attn_decode_append")) return -1;
+        for (int p = 0; p < r; ++p)
+            if (reqids[p] == reqids[r]) { set_error("attn_decode_append: a reqId appears twice in the batch"); return -1; }
+    }
+    const NewRows fresh{k_new, v_new};
+    return decode_common(ctx, layer, stream, q, o, reqids, kv_lens, n, scale, workspace, workspace_bytes, nullptr, &fresh, "attn_decode_append");
 }
 
 int vattn_attn_decode_paged(vattn_ctx* ctx, void* stream, const void* q, void* o, const void* k_pool, const void* v_pool,
@@ -298,7 +315,7 @@ int vattn_attn_decode_paged(vattn_ctx* ctx, void* stream, const void* q, void* o
         }
     }
     const PagedKv pk{k_pool, v_pool, num_blocks, block_tokens, block_table, max_blocks_per_req};
-    return decode_common(ctx, 0, stream, q, o, nullptr, kv_lens, n, scale, workspace, workspace_bytes, &pk, "attn_decode_paged");
+    return decode_common(ctx, 0, stream, q, o, nullptr, kv_lens, n, scale, workspace, workspace_bytes, &pk, nullptr, "attn_decode_paged");
 }
 
 int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
@@ -308,8 +325,8 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
     if (n == 0) return 0;
     if (cu_q[0] != 0) { set_error("attn_prefill: cu_q[0] must be 0"); return -1; }
     const int H = ctx->cfg.num_kv_heads, Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
-    // 128 query rows per work item by default; the wide kernel (256 rows, one workgroup per CU,
-    // software-pipelined) is opt-in: measured equal on long prompts and slower on short ones.
+    // 256 query rows per work item for both kernels; the wide one (four waves of 64 rows, software-pipelined)
+    // is opt-in: measured slower.
     const bool wide = ctx->prefill_wide;
     const int BM = wide ? 256 : kPrefillRows;
     for (int r = 0; r < n; ++r) {

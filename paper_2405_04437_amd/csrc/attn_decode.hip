@@ -227,9 +227,26 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
     // (A second register set, two tiles in flight, was measured and bought nothing: with 8 waves per CU
     // the memory system is already saturated.)
     issue_loads(kreg, vreg, 0);
+    // Fused KV append (optional): the request's newest token, position kv_len - 1, has not been written to the
+    // cache yet.  The one wave whose piece holds that token for this KV head puts the row into its LDS tile
+    // (over whatever the cache held there) and into the cache, K by lanes 0 .. LPR-1, V by the next LPR lanes.
+    const int last_local = a.k_new != nullptr && !PAGED ? kv_len - 1 - tok0 : -1;   // token index inside the piece, or out of reach
     for (int t = 0; t < ntiles; ++t) {
         stage(kreg, vreg);
         if (t + 1 < ntiles) issue_loads(kreg, vreg, t + 1);
+        if (last_local >= t * kTile && last_local < (t + 1) * kTile) {   // uniform; true for at most one tile of one piece
+            if (l < 2 * G::LPR) {
+                const bool is_v = l >= G::LPR;
+                const int c = (l % G::LPR) * 16;
+                const char* src = static_cast<const char*>(is_v ? a.v_new : a.k_new) + (static_cast<int64_t>(req) * a.H + kvh) * G::RB + c;
+                const u32x4 x = *reinterpret_cast<const u32x4*>(src);
+                const int row = last_local - t * kTile;
+                *reinterpret_cast<u32x4*>((is_v ? vlds + row * G::VSTR : klds + row * G::KSTR) + c) = x;
+                *reinterpret_cast<u32x4*>(const_cast<char*>(is_v ? vp : kp) + static_cast<int64_t>(kv_len - 1) * row_stride + c) = x;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
         compute(t);
     }
 

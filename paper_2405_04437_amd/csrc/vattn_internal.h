@@ -93,6 +93,8 @@ struct DecodeArgs {
     // Paged comparison variant only: k_base / v_base are block pools [num_blocks, block_tokens, H, D] and
     // block_table[req * table_stride + j] names the block holding tokens j*block_tokens .. of batch slot req.
     const int32_t* block_table; int table_stride; int block_tokens;
+    // Fused append only: newest K/V rows [n, H, D] of the batch, to be stored at position kv_len - 1 (else null).
+    const void* k_new; const void* v_new;
 };
 int decode_resident_workgroups(int Hq, int H, int D, int num_cus);  // workgroups one launch keeps resident
 bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});   // paged if a.block_table

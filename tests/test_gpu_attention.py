@@ -187,3 +187,42 @@ def test_config2_yi6b_decode_full_size_matches_oracle():
     wl = W.config(1)
     got, want, _ = _run_decode(wl.shape, wl.kv_lens, wl.seed)
     check(got, want, "C2 decode")
+
+
+@pytest.mark.parametrize("Hq,H,D", [(32, 4, 128), (40, 2, 64), (56, 8, 128)])
+def test_decode_with_fused_append_matches_oracle_and_fills_the_cache(Hq, H, D):
+    """vattn_attn_decode_append = append_kv + attn_decode in one launch: the newest token's K/V rows are taken
+    from the caller's buffers, attended to, and stored at position kv_len-1 of the cache."""
+    import torch
+    import paper_2405_04437_amd as P
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
+
+    shape = W.Shape("t", Hq, H, D, 1)
+    kv_lens = [1, 2, 32, 33, 64, 65, 1000, 2049, 4096]      # newest token first / last in a tile, alone, across segments
+    n = len(kv_lens)
+    inp = W.draw_attention_inputs(shape, [1] * n, kv_lens, seed=Hq + D)
+    scale = W.softmax_scale(D)
+    s = _session(shape, n, max(kv_lens))
+    ids = [s.admit(L) for L in kv_lens]
+    s.step()
+    # the cache holds everything but the newest token of each request; its slot holds a poison pattern
+    old_k = [k[:-1] for k in inp.k]
+    old_v = [v[:-1] for v in inp.v]
+    cu = np.zeros(n + 1, dtype=np.int64); cu[1:] = np.cumsum([L - 1 for L in kv_lens])
+    if cu[-1]:
+        s.append(0, bits_to_tensor(np.concatenate(old_k)), bits_to_tensor(np.concatenate(old_v)), ids, cu, [0] * n)
+    poison = torch.full((n, H, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    s.append(0, poison, poison, ids, np.arange(n + 1), [L - 1 for L in kv_lens])
+    k_new = bits_to_tensor(np.stack([k[-1] for k in inp.k]))
+    v_new = bits_to_tensor(np.stack([v[-1] for v in inp.v]))
+    q = bits_to_tensor(inp.q)
+    o = torch.empty_like(q)
+    ws = s.workspace(kv_lens)
+    rc = s.va.attn_decode_append(0, s.stream, q, k_new, v_new, o, ids, kv_lens, scale, ws, ws.numel())
+    assert rc == 0, P.last_error()
+    want = OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale)
+    check(tensor_to_f32(o), want, "fused append + decode")
+    # the cache now holds the new rows: a plain decode over it gives the same answer
+    check(tensor_to_f32(s.decode(0, q, ids, kv_lens, scale)), want, "plain decode after the fused append")
+    assert s.va.attn_decode_append(0, s.stream, q[:2], k_new[:2], v_new[:2], o[:2], [ids[0], ids[0]], kv_lens[:2], scale, ws, ws.numel()) == -1
+    s.close()
