@@ -132,11 +132,11 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
         seq[ids] = lens + 1
         assert va.step(seq) == 0
         att = i % layers                  # the layer attended to in this step; its append rides in the decode kernel
-        for layer in range(layers):
+        assert va.attn_decode_append(att, stream, q, knew, vnew, o, ids, lens + 1, scale, ws, ws.numel()) == 0
+        for layer in range(layers):       # the other layers' appends are independent of it and queue up behind
             if layer != att:
                 assert va.append_kv(layer, stream, knew, vnew, ids, cu, lens) == 0
         lens[:] += 1
-        assert va.attn_decode_append(att, stream, q, knew, vnew, o, ids, lens, scale, ws, ws.numel()) == 0
         # iteration boundary of the serving loop (Algorithm 1): the framework needs this iteration's
         # output on the host before it can schedule the next one
         torch_stream.synchronize()
