@@ -6,9 +6,9 @@
 //
 // gfx950 mapping
 //  * One workgroup (kPrefillWaves = 8 waves, one workgroup per CU, two waves per SIMD) owns 256 query
-//    rows of one query head, 32 per wave; all eight waves share each K/V tile.  KV is
-//    walked in tiles of 64 tokens, double buffered in LDS; tile t+1 travels from global memory straight
-//    into LDS (buffer loads with the LDS bit) while tile t is being multiplied.
+//    rows of one query head, 32 per wave; all eight waves share each K/V tile.  KV is walked in tiles
+//    of 64 tokens through a four-stage LDS ring, two tiles per workgroup barrier; tiles travel from
+//    global memory straight into LDS (buffer loads with the LDS bit) two tiles ahead of their use.
 //  * Both contractions use v_mfma_f32_32x32x16_bf16.  Scores are produced transposed,
 //    S^T = K Q^T (tokens x rows): a lane then owns ONE query row, so the running max / sum are
 //    per-lane scalars (one cross-lane exchange per tile), and exp(S^T) is already laid out as the B
@@ -54,7 +54,8 @@ template <int D> struct PGeo {
     static constexpr int NLW = (NB + kWaves - 1) / kWaves;   // at most this many per wave
     static constexpr int KV = kBN * RB;                      // one K (or V) tile in LDS, rows unpadded
     static constexpr int BUF = 2 * KV;                       // one K+V stage
-    static constexpr int LDS = 2 * BUF;
+    static constexpr int STAGES = 4;                         // two tiles being read, two arriving
+    static constexpr int LDS = STAGES * BUF;
     // Rows are stored unpadded (the loads below write LDS directly, 1 KiB contiguous per instruction), so
     // bank conflicts are avoided by permuting the 16-byte chunks inside each row instead: chunk c of row r
     // is stored at chunk position c ^ swz(r).  LDS has 64 banks of 4 bytes, i.e. 256 bytes per clock:
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
         // raw buffer resource: base[47:0], stride 0, num_records, data format word
         const u32x4 krs = {static_cast<uint32_t>(ka), static_cast<uint32_t>(ka >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
         const u32x4 vrs = {static_cast<uint32_t>(va), static_cast<uint32_t>(va >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
-        const uint32_t kb = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + (t & 1) * G::BUF;   // LDS byte address
+        const uint32_t kb = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + (t & (G::STAGES - 1)) * G::BUF;   // LDS byte address
 #pragma unroll
         for (int j = 0; j < G::NLW; ++j) {
             const int b = w + j * kWaves;                 // scalar: which 1 KiB block of the tile
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
     f32x16 s[2];
     auto wave_active = [&](int t) { return t * kBN <= wave_last_key && row_lo < q_len; };
     auto tile_scores = [&](int t) {
-        const char* kb = lds + (t & 1) * G::BUF;
+        const char* kb = lds + (t & (G::STAGES - 1)) * G::BUF;
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
@@ -214,7 +215,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
         __builtin_amdgcn_s_setprio(0);
     };
     auto tile_softmax_pv = [&](int t) {
-        const char* vb = lds + (t & 1) * G::BUF + G::KV;
+        const char* vb = lds + (t & (G::STAGES - 1)) * G::BUF + G::KV;
         const int t0 = t * kBN;
         bf16x8 pb[4];
         // lane owns query row my_row; s[tb][i] is token t0 + tb*32 + (i/4)*8 + (l/32)*4 + i%4
@@ -288,20 +289,26 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
         __builtin_amdgcn_s_setprio(0);
     };
 
+    // Four-stage LDS ring, tile x in stage x % 4, walked two tiles per iteration: one workgroup barrier per
+    // 128 tokens.  Tiles t+2 and t+3 go into the stages of tiles t-2 and t-1, which every wave finished
+    // reading before the last barrier; a tile index past the end is out of range for every lane and only
+    // writes zeros.
     issue_loads(0);
-    // everything requested so far - Q and tile 0 - has landed before the loop starts
+    issue_loads(1);
+    // everything requested so far - Q and the first two tiles - has landed before the loop starts
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
     __syncthreads();
 
-    for (int t = 0; t < ntiles; ++t) {
-        // tile t+1 goes into the other stage, which every wave finished reading before the last barrier;
-        // a tile index past the end is out of range for every lane and only writes zeros
-        issue_loads(t + 1);
-        if (wave_active(t)) {
-            tile_scores(t);
-            tile_softmax_pv(t);
-        }
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's part of tile t+1 is in LDS
+    for (int t = 0; t < ntiles; t += 2) {
+        issue_loads(t + 2);
+        issue_loads(t + 3);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            if (wave_active(t + u)) {     // false for t + u >= ntiles as well
+                tile_scores(t + u);
+                tile_softmax_pv(t + u);
+            }
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's parts of the two new tiles are in LDS
         __syncthreads();
     }
 
