@@ -11,7 +11,8 @@
      time, its maximum, and where the map calls happened);
   4. deferred reclamation + eager allocation: time from "request arrives" to "prefill may start"
      (alloc_reqid + step) with pages unmapped on free, deferred, and deferred + eager;
-  5. the decode kernel over contiguous KV vs its paged comparison variant (block table inside the kernel).
+  5. the decode kernel over contiguous KV vs its paged comparison variant (block table inside the kernel);
+  6. the decode kernel over the all-layers-in-one-buffer layout (tensor slicing, strided tokens).
 
 Everything runs through the C ABI (paper_2405_04437_amd.binding); no result is checked here - parity lives in
 tests/.  Usage: python paper_2405_04437_amd/vmm_report.py [--quick]
@@ -149,6 +150,51 @@ def paged_overhead(P, torch, W, quick):
     print()
 
 
+def slicing_effect(P, torch, W, quick):
+    print("## 6. Tensor slicing: decode kernel over [L, N, H, D] (all layers in one buffer) vs [L, H, D] per layer\n")
+    print("Yi-6B shape, 32 requests x 4096 tokens, 2 MiB page-groups.  With N layers in one buffer consecutive tokens of")
+    print("a layer are N KiB apart and a page-group holds 2048/N tokens of every layer.\n")
+    print("| layout | tokens per page-group | page-groups mapped (all buffers) | split-K kernel us | GB/s |")
+    print("|---|---|---|---|---|")
+    from paper_2405_04437_amd.runtime import KvSession
+
+    shape = W.YI_6B
+    n, ctx, G = 32, 4096, 2 * MiB
+    for name, layers, flags in (("per-layer buffers, N = 8", 8, 0), ("one buffer, N = 8", 8, P.FLAG_TENSOR_SLICING),
+                                ("one buffer, N = 32", 32, P.FLAG_TENSOR_SLICING)):
+        sliced = bool(flags)
+        tok = shape.token_bytes * (layers if sliced else 1)
+        per_req = ((ctx + 64) * tok + G - 1) // G * G
+        s = KvSession(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, n, ctx + 64,
+                      per_req * 2 * (1 if sliced else layers) * n, layers, G, flags=flags)
+        gen = torch.Generator(device="cuda"); gen.manual_seed(1)
+        ids = [s.admit(ctx) for _ in range(n)]
+        s.step()
+        k = torch.randn((ctx, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+        for r in ids:
+            for layer in (0, layers - 1):
+                s.append(layer, k, k, [r], [0, ctx], [0])
+        q = torch.randn((n, shape.num_q_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+        o = torch.empty_like(q)
+        lens = [ctx] * n
+        ws = s.workspace(lens)
+        scale = W.softmax_scale(shape.head_dim)
+        for i in range(20):
+            s.decode((layers - 1) * (i & 1), q, ids, lens, scale, out=o, ws=ws)
+        torch.cuda.synchronize()
+        s.va.set_timing(True); s.va.kernel_time(0)
+        for i in range(100):
+            s.decode((layers - 1) * (i & 1), q, ids, lens, scale, out=o, ws=ws)
+        torch.cuda.synchronize()
+        ms, cnt = s.va.kernel_time(0)
+        us = ms * 1e3 / cnt
+        nbytes = n * ctx * 2 * shape.token_bytes
+        mapped = s.va.counters()[0]
+        print(f"| {name} | {G // tok} | {mapped} | {us:.1f} | {nbytes / us / 1e3:.0f} |")
+        s.close()
+    print()
+
+
 def latency_hiding(P, torch, W, quick):
     print("## 3. Synchronous step() vs background look-ahead (decode loop, 32 requests, 256 KiB page-groups)\n")
     print("Every request crosses a page-group boundary every 256 tokens; the 32 requests start at staggered offsets, so")
@@ -263,6 +309,7 @@ def main() -> int:
     latency_hiding(P, torch, W, args.quick)
     prefill_admission(P, torch, W, args.quick)
     paged_overhead(P, torch, W, args.quick)
+    slicing_effect(P, torch, W, args.quick)
     return 0
 
 
