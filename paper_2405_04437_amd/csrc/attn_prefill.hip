@@ -233,7 +233,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[tb][i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;   // scale > 0: max commutes with scaling
+        // the row's other half lives in lane l ^ 32: v_permlane32_swap exchanges the wave halves of two
+        // registers in the vector unit (a cross-lane shuffle would go through LDS and its latency sits on
+        // the critical path of the softmax); scale > 0: max commutes with scaling
+        {
+            const unsigned bits = __builtin_bit_cast(unsigned, mx);
+            const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);   // {lo,lo}, {hi,hi}
+            mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1])) * scale_log2;
+        }
         // Query rows past q_len hold a copy of the last row's Q, and key 0 is visible to every row, so
         // the first tile always raises m from -inf to a finite value for all lanes.
         if (__builtin_amdgcn_ballot_w64(mx > m + kLazy) != 0) {
