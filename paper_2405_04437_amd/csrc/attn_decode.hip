@@ -55,7 +55,17 @@ template <int D> struct Geo {
     static constexpr int WAVE_LDS = kTile * (KSTR + VSTR);
 };
 
-__device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask)); }
+// Maximum over the four 16-lane rows of the wave (lanes with equal l % 16), in every lane.  v_permlane16_swap
+// / v_permlane32_swap exchange rows / halves of two registers inside the vector unit; a cross-lane shuffle
+// would take a round trip through LDS for each of the two steps.
+__device__ __forceinline__ float row_group_max(float v) {
+    const unsigned b0 = __builtin_bit_cast(unsigned, v);
+    const auto s16 = __builtin_amdgcn_permlane16_swap(b0, b0, false, false);     // {r0,r0,r2,r2}, {r1,r1,r3,r3}
+    v = fmaxf(__builtin_bit_cast(float, s16[0]), __builtin_bit_cast(float, s16[1]));
+    const unsigned b1 = __builtin_bit_cast(unsigned, v);
+    const auto s32 = __builtin_amdgcn_permlane32_swap(b1, b1, false, false);     // {lo,lo}, {hi,hi}
+    return fmaxf(__builtin_bit_cast(float, s32[0]), __builtin_bit_cast(float, s32[1]));
+}
 
 // INL: the index arrays are read from the kernel-argument segment (InlineMeta) instead of global memory;
 // a compile-time switch so that both variants keep these uniform reads on the scalar unit.
@@ -188,8 +198,7 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
                 s[r][i] = x;
                 mx = fmaxf(mx, x);
             }
-        mx = xor_max(mx, 16);
-        mx = xor_max(mx, 32);
+        mx = row_group_max(mx);
         const float m_new = fmaxf(m, mx);           // finite: every tile holds at least one valid token
         const float alpha = __builtin_amdgcn_exp2f(m - m_new);
         m = m_new;

@@ -177,7 +177,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_wide_kernel(PrefillArgs a
         float mx = s[0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
-        return fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+        const unsigned bits = __builtin_bit_cast(unsigned, mx);
+        const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);   // wave halves exchanged in the vector unit
+        return fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1])) * scale_log2;
     };
     auto rescale = [&](int qa, float mx) {
         const float m_new = fmaxf(m[qa], mx);
