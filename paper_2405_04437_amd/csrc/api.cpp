@@ -328,7 +328,15 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
     // 256 query rows per work item for both kernels; the wide one (four waves of 64 rows, software-pipelined)
     // is opt-in: measured slower.
     const bool wide = ctx->prefill_wide;
-    const int BM = wide ? 256 : kPrefillRows;
+    // Default kernel: twelve waves (384 rows per work item, three waves per SIMD) when that still leaves
+    // every CU several work items, else eight waves (256 rows).
+    int waves = 8;
+    if (!wide) {
+        int64_t items12 = 0;
+        for (int r = 0; r < n; ++r) items12 += (static_cast<int64_t>(cu_q[r + 1]) - cu_q[r] + 383) / 384 * Hq;
+        if (items12 >= 4 * static_cast<int64_t>(ctx->num_cus)) waves = 12;
+    }
+    const int BM = wide ? 256 : 32 * waves;
     for (int r = 0; r < n; ++r) {
         const int64_t ql = static_cast<int64_t>(cu_q[r + 1]) - cu_q[r];
         if (ql < 0) { set_error("attn_prefill: cu_q must be non-decreasing"); return -1; }
@@ -384,7 +392,7 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
     a.cu_q = reinterpret_cast<const int32_t*>(d + off_cu);
     a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
     a.items = reinterpret_cast<const PrefillItem*>(d + off_items);
-    a.items_per_xcd = static_cast<int>(per_xcd); a.n = n; a.scale = scale;
+    a.items_per_xcd = static_cast<int>(per_xcd); a.n = n; a.scale = scale; a.waves = waves;
     LaunchEvents ev;
     if (ctx->timing && !ctx->timers[1].next(&ev.start, &ev.stop)) return -1;
     if (!(wide ? launch_prefill_wide(a, s, ev) : launch_prefill(a, s, ev))) return -1;

@@ -5,8 +5,9 @@
 // sub-tensor at base + reqId*S (Sec. 5.2.3): no block table, one pointer and one stride.
 //
 // gfx950 mapping
-//  * One workgroup (kPrefillWaves = 8 waves, one workgroup per CU, two waves per SIMD) owns 256 query
-//    rows of one query head, 32 per wave; all eight waves share each K/V tile.  KV is walked in tiles
+//  * One workgroup per CU: 8 waves (two per SIMD, 256 query rows of one query head) or, when the launch
+//    has enough work items to keep every CU busy for several rounds, 12 waves (three per SIMD, 384 rows);
+//    32 rows per wave, all waves share each K/V tile.  KV is walked in tiles
 //    of 64 tokens through a four-stage LDS ring, two tiles per workgroup barrier; tiles travel from
 //    global memory straight into LDS (buffer loads with the LDS bit) two tiles ahead of their use.
 //  * Both contractions use v_mfma_f32_32x32x16_bf16.  Scores are produced transposed,
@@ -35,9 +36,6 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 constexpr int kBN = 64;    // KV tokens per tile
-constexpr int kAhead = 6;               // matrix operands requested from LDS this many multiplies ahead
-constexpr int kWaves = kPrefillWaves;   // waves per workgroup, 32 query rows each
-constexpr int kThreads = kWaves * 64;
 constexpr float kLog2e = 1.4426950408889634f;
 // The running maximum is only raised when some row's tile maximum exceeds it by more than this many
 // binary orders of magnitude: exponentials then stay below 2^kLazy, which fp32 sums and bf16 P hold
@@ -46,12 +44,13 @@ constexpr float kLazy = 8.0f;
 // Fourth dword of a gfx9-family raw buffer resource: 32-bit data format, no swizzle, no stride.
 constexpr int kRsrcWord3 = 0x00020000;
 
-template <int D> struct PGeo {
+// D: head dimension; NW: waves per workgroup (8 or 12), 32 query rows each.
+template <int D, int NW> struct PGeo {
     static constexpr int RB = D * 2;                         // bytes per head row
     static constexpr int CH = RB / 16;                       // 16-byte chunks per row
     static constexpr int RPW = 1024 / RB;                    // rows one wave-wide 16 B/lane load covers
-    static constexpr int NB = kBN / RPW;                     // such loads per tile and tensor; wave w issues loads w, w+kWaves, ...
-    static constexpr int NLW = (NB + kWaves - 1) / kWaves;   // at most this many per wave
+    static constexpr int NB = kBN / RPW;                     // such loads per tile and tensor; wave w issues loads w, w+NW, ...
+    static constexpr int NLW = (NB + NW - 1) / NW;           // at most this many per wave
     static constexpr int KV = kBN * RB;                      // one K (or V) tile in LDS, rows unpadded
     static constexpr int BUF = 2 * KV;                       // one K+V stage
     static constexpr int STAGES = 4;                         // two tiles being read, two arriving
@@ -69,10 +68,14 @@ template <int D> struct PGeo {
 
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a) {
-    using G = PGeo<D>;
-    constexpr int BM = kPrefillRows;           // query rows per workgroup
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a) {
+    using G = PGeo<D, NW>;
+    constexpr int kWaves = NW;
+    // matrix operands are requested from LDS this many multiplies ahead; three waves per SIMD leave 168
+    // registers per lane, which a depth of 6 does not fit
+    constexpr int kAhead = NW > 8 ? 4 : 6;
+    constexpr int BM = NW * 32;                // query rows per workgroup
     constexpr int WR = 32;                     // query rows per wave
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
@@ -343,16 +346,19 @@ bool launch_prefill(const PrefillArgs& a_in, hipStream_t stream, LaunchEvents ev
     dim3 grid(static_cast<unsigned>(8 * a_in.items_per_xcd * group));
     if (grid.x == 0) return true;
     const PrefillArgs& a = a_in;
-    static bool allowed[2] = {false, false};  // per kernel variant
+    static bool allowed[4] = {};  // per kernel variant
     auto launch = [&](auto kernel, int lds, int variant) -> bool {
         if (!allowed[variant]) {  // dynamic LDS above 64 KiB has to be allowed once per kernel
             if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds), "hipFuncSetAttribute")) return false;
             allowed[variant] = true;
         }
-        hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), static_cast<size_t>(lds), stream, ev.start, ev.stop, 0, a);
+        hipExtLaunchKernelGGL(kernel, grid, dim3(static_cast<unsigned>(a.waves * 64)), static_cast<size_t>(lds), stream, ev.start, ev.stop, 0, a);
         return true;
     };
-    if (!(a.D == 128 ? launch(prefill_kernel<128>, PGeo<128>::LDS, 0) : launch(prefill_kernel<64>, PGeo<64>::LDS, 1))) return false;
+    bool ok;
+    if (a.waves == 12) ok = a.D == 128 ? launch(prefill_kernel<128, 12>, PGeo<128, 12>::LDS, 2) : launch(prefill_kernel<64, 12>, PGeo<64, 12>::LDS, 3);
+    else ok = a.D == 128 ? launch(prefill_kernel<128, 8>, PGeo<128, 8>::LDS, 0) : launch(prefill_kernel<64, 8>, PGeo<64, 8>::LDS, 1);
+    if (!ok) return false;
     return hip_ok(hipGetLastError(), "prefill launch");
 }
 

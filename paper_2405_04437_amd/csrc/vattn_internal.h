@@ -109,14 +109,14 @@ struct PrefillArgs {
     const int32_t* reqids; const int32_t* cu_q; const int32_t* kv_lens;   // device
     const PrefillItem* items;               // device: 8 queues of items_per_xcd entries each
     int items_per_xcd; int n;
+    int waves;                              // default kernel: waves per workgroup (8 or 12); a work item is 32*waves rows
     float scale;
 };
-// Two kernels: the default with kPrefillWaves waves x 32 query rows per work item, and a wide one with
-// 4 waves x 64 rows (software-pipelined).  Both take 256 rows per work item, one workgroup per CU.
-// Measured on C3 / C5 for the default: 8 waves 1.12 / 1.17 PFLOP/s; 4 waves (two workgroups per CU)
-// 1.07 / 1.12; 6 waves at three waves per SIMD (fewer registers, shallower operand prefetch) 0.97 / 1.00.
-constexpr int kPrefillWaves = 8;
-constexpr int kPrefillRows = kPrefillWaves * 32;
+// Two kernels: the default with 32 query rows per wave and `waves` = 8 or 12 waves per work item, and a
+// wide one with 4 waves x 64 rows (software-pipelined); one workgroup per CU in all cases.
+// Measured on C3 / C5 for the default: 12 waves (three per SIMD) 1.18 / 1.22 PFLOP/s, 8 waves 1.13 / 1.19;
+// 4 waves with two workgroups per CU 1.07 / 1.12; 6 waves at three per SIMD in two workgroups 0.97 / 1.00.
+// Twelve waves need many work items: a 2048-token chunk (C4) runs 20 % slower with them than with eight.
 bool launch_prefill(const PrefillArgs& a, hipStream_t stream, LaunchEvents ev = {});
 bool launch_prefill_wide(const PrefillArgs& a, hipStream_t stream, LaunchEvents ev = {});
 

@@ -44,7 +44,7 @@ def _randn_bf16(torch, gen, shape):
 
 def _boundaries(q_len, off, shape):
     page_tokens = 2 * MiB // shape.token_bytes
-    b = [128, 256, 512, q_len - 512, 64 - off % 64, 2 * page_tokens - off, page_tokens - off, q_len - 256, q_len - 128, q_len - 64]
+    b = [128, 256, 384, 512, 768, q_len - 512, q_len - 384, 64 - off % 64, 2 * page_tokens - off, page_tokens - off, q_len - 256, q_len - 128, q_len - 64]
     return [x for x in b if 0 < x < q_len]
 
 
@@ -179,4 +179,35 @@ def test_config5_long_context_prefill_then_decode():
         want_d = OA.attention_request(tensor_to_bits(qd), np.concatenate(ks), np.concatenate(vs), scale)
         check(tensor_to_f32(od), want_d, f"C5 decode step {step}")
     assert sess.va.query(rid)[1] == pages_before + 1   # 131072 tokens fill 128 page-groups exactly; token 131073 maps the 129th
+    sess.close()
+
+
+@pytest.mark.parametrize("Hq,H,D", [(16, 4, 64), (32, 8, 128)])
+def test_many_work_items_take_the_twelve_wave_kernel(Hq, H, D):
+    """Launches with many work items run 384 query rows per workgroup (twelve waves); ragged prompt lengths,
+    one of them a chunk appended to an existing context, both head dimensions.  Sampled rows."""
+    import torch
+    from paper_2405_04437_amd.runtime import tensor_to_bits, tensor_to_f32
+
+    shape = W.Shape("t", Hq, H, D, 1)
+    scale = W.softmax_scale(D)
+    q_lens = [9001, 7999, 7700, 383] if D == 64 else [5000, 4097, 3500, 385]
+    offs = [0, 0, 1000, 0]
+    kv_lens = [q + o for q, o in zip(q_lens, offs)]
+    assert sum((q + 383) // 384 for q in q_lens) * Hq >= 4 * 256
+    gen = torch.Generator(device="cuda"); gen.manual_seed(D)
+    sess = _session(shape, len(q_lens), max(kv_lens))
+    ids = [sess.admit(L) for L in kv_lens]
+    sess.step()
+    kv = [_fill(sess, torch, gen, shape, r, L, keep=True) for r, L in zip(ids, kv_lens)]
+    cu = np.zeros(len(q_lens) + 1, dtype=np.int64); cu[1:] = np.cumsum(q_lens)
+    q = torch.cat([_randn_bf16(torch, gen, (L, Hq, D)) for L in q_lens])
+    o = sess.prefill(0, q, ids, cu, kv_lens, scale)
+    torch.cuda.synchronize()
+    for r in range(len(q_lens)):
+        rows = W.sample_rows(q_lens[r], 96, seed=r, boundaries=_boundaries(q_lens[r], offs[r], shape))
+        qb = tensor_to_bits(q[int(cu[r]):int(cu[r + 1])])
+        want = OA.attention_request(qb, kv[r][0], kv[r][1], scale, rows=rows)
+        got = tensor_to_f32(o[int(cu[r]):int(cu[r + 1])][torch.from_numpy(rows.astype(np.int64)).cuda()])
+        check(got, want, f"12-wave prefill D={D} prompt {r}")
     sess.close()
