@@ -40,7 +40,8 @@ def _load() -> ctypes.CDLL:
         raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2405_04437_amd/build.py` "
                           "(or __graft_entry__.build()); there is no CPU fallback")
     lib = ctypes.CDLL(LIB_PATH)
-    vp, i32p, i64p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+    # host index arrays (int32 / int64) are passed as addresses, see _host_array
+    vp, i32p, i64p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
     dp = ctypes.POINTER(ctypes.c_double)
     lib.vattn_last_error.restype = ctypes.c_char_p
     lib.vattn_init.argtypes = [ctypes.POINTER(_Config), ctypes.POINTER(vp)]
@@ -92,14 +93,21 @@ def last_error() -> str:
     return (lib.vattn_last_error() or b"").decode()
 
 
+def _host_array(a, dtype):
+    """(array kept alive by the caller, its address): host index arrays are passed as plain addresses; an
+    array that already has the right type and layout is used as it is (these calls sit on the critical
+    path of a serving loop, between two GPU iterations)."""
+    if type(a) is not np.ndarray or a.dtype != dtype or not a.flags.c_contiguous:
+        a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.__array_interface__["data"][0]
+
+
 def _i32(a: Sequence[int]):
-    arr = np.ascontiguousarray(a, dtype=np.int32)
-    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    return _host_array(a, np.int32)
 
 
 def _i64(a: Sequence[int]):
-    arr = np.ascontiguousarray(a, dtype=np.int64)
-    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+    return _host_array(a, np.int64)
 
 
 def _ptr(x) -> int:
@@ -212,7 +220,7 @@ class Vattn:
         t = np.ascontiguousarray(block_table, dtype=np.int32)
         k, kp = _i64(kv_lens)
         return lib.vattn_attn_decode_paged(self._h, stream, _ptr(q), _ptr(o), _ptr(k_pool), _ptr(v_pool), num_blocks,
-                                           block_tokens, t.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), t.shape[1],
+                                           block_tokens, t.ctypes.data, t.shape[1],
                                            kp, len(k), scale, _ptr(workspace), workspace_bytes)
 
     # ---- measurement -----------------------------------------------------------------------
