@@ -319,7 +319,9 @@ def main() -> int:
         out["roofline"] = {"kernel": "decode_splitk_kernel<128>", "bound": "hbm", "achieved": r["gbs_kernel"],
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": r["gbs_kernel"] / HBM_PEAK_GBS,
                            "avg_launch_ms": r["kernel_ms"], "algorithmic_bytes_per_launch": r["kbytes_per_launch"],
-                           "traffic": _measured_traffic("decode_splitk_C2")}
+                           "traffic": (_measured_traffic("decode_splitk_C2") or {}).get("total_bytes"),
+                           "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
+                           "traffic_detail": _measured_traffic("decode_splitk_C2")}
         if "cpu_baseline" in r:
             out["cpu_baseline"] = r.pop("cpu_baseline")
         out["decode_detail"] = {k: r[k] for k in ("reduce_ms", "tokens_in_batch", "map_calls_in_timed_region",
@@ -331,7 +333,8 @@ def main() -> int:
                                         "frac_of_bf16_mfma_peak": p["frac_of_mfma_peak"], "ms": p["ms_per_call"],
                                         "kernel_ms": p["kernel_ms"], "q_tokens": p["q_tokens"],
                                         "flop_convention": "causal only: 4*Hq*D per visible (query,key) pair",
-                                        "traffic": _measured_traffic("prefill_C3")}
+                                        "traffic": (_measured_traffic("prefill_C3") or {}).get("total_bytes"),
+                                        "traffic_detail": _measured_traffic("prefill_C3")}
     if args.only == "all":
         wl4 = W.config(3)
         d4 = run_decode(args, torch, W, wl4, max(10, args.steps // 10), 10, layers=1, with_oracle=False, churn=True)
