@@ -215,6 +215,14 @@ int vattn_attn_decode_paged(vattn_ctx* ctx, void* stream, const void* q /*device
                             const int64_t* kv_lens /*host*/, int n, float scale, void* workspace /*device*/,
                             size_t workspace_bytes);
 
+/* The same comparison for prefill: the default prefill kernel with a block-table lookup per 64-token
+ * tile.  Arguments as for vattn_attn_decode_paged and vattn_attn_prefill; block_tokens: a multiple of 64;
+ * kv_lens[r] counts the query tokens, which must already be in the pools. */
+int vattn_attn_prefill_paged(vattn_ctx* ctx, void* stream, const void* q /*device*/, void* o /*device*/,
+                             const void* k_pool /*device*/, const void* v_pool /*device*/, int64_t num_blocks,
+                             int block_tokens, const int32_t* block_table /*host*/, int max_blocks_per_req,
+                             const int32_t* cu_q /*host*/, const int64_t* kv_lens /*host*/, int n, float scale);
+
 /* ---- measurement helpers --------------------------------------------------------------------- */
 
 /* When enabled, every launch of the split-K decode kernel, the reduce kernel and the prefill kernel

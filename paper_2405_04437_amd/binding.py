@@ -64,6 +64,8 @@ def _load() -> ctypes.CDLL:
                                              ctypes.c_size_t]
     lib.vattn_attn_decode_paged.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, i32p, ctypes.c_int, i64p,
                                             ctypes.c_int, ctypes.c_float, vp, ctypes.c_size_t]
+    lib.vattn_attn_prefill_paged.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, i32p, ctypes.c_int, i32p, i64p,
+                                             ctypes.c_int, ctypes.c_float]
     lib.vattn_set_timing.argtypes = [vp, ctypes.c_int]
     lib.vattn_kernel_time.argtypes = [vp, ctypes.c_int, dp, i64p]
     lib.vattn_set_decode_chunk.argtypes = [vp, ctypes.c_int]
@@ -75,7 +77,7 @@ def _load() -> ctypes.CDLL:
     for name in ("vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_query",
                  "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill", "vattn_attn_decode",
                  "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide",
-                 "vattn_step_counters", "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append"):
+                 "vattn_step_counters", "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -86,7 +88,7 @@ EXPORTED = ["vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqi
             "vattn_query", "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill",
             "vattn_decode_workspace_bytes", "vattn_attn_decode", "vattn_set_timing", "vattn_kernel_time",
             "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide", "vattn_step_counters",
-            "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_last_error"]
+            "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged", "vattn_last_error"]
 
 
 def last_error() -> str:
@@ -222,6 +224,14 @@ class Vattn:
         return lib.vattn_attn_decode_paged(self._h, stream, _ptr(q), _ptr(o), _ptr(k_pool), _ptr(v_pool), num_blocks,
                                            block_tokens, t.ctypes.data, t.shape[1],
                                            kp, len(k), scale, _ptr(workspace), workspace_bytes)
+
+    def attn_prefill_paged(self, stream: int, q, o, k_pool, v_pool, num_blocks: int, block_tokens: int, block_table,
+                           cu_q, kv_lens, scale: float) -> int:
+        t = np.ascontiguousarray(block_table, dtype=np.int32)
+        c, cp = _i32(cu_q)
+        k, kp = _i64(kv_lens)
+        return lib.vattn_attn_prefill_paged(self._h, stream, _ptr(q), _ptr(o), _ptr(k_pool), _ptr(v_pool), num_blocks,
+                                            block_tokens, t.ctypes.data, t.shape[1], cp, kp, len(k), scale)
 
     # ---- measurement -----------------------------------------------------------------------
     def set_timing(self, enabled: bool) -> int:

@@ -318,16 +318,18 @@ int vattn_attn_decode_paged(vattn_ctx* ctx, void* stream, const void* q, void* o
     return decode_common(ctx, 0, stream, q, o, nullptr, kv_lens, n, scale, workspace, workspace_bytes, &pk, nullptr, "attn_decode_paged");
 }
 
-int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
-                       const int32_t* cu_q, const int64_t* kv_lens, int n, float scale) {
-    if (!check_ctx_layer(ctx, layer, "attn_prefill")) return -1;
-    if (n < 0 || (n > 0 && (!q || !o || !reqids || !cu_q || !kv_lens))) { set_error("attn_prefill: null argument"); return -1; }
-    if (n == 0) return 0;
-    if (cu_q[0] != 0) { set_error("attn_prefill: cu_q[0] must be 0"); return -1; }
+}  // extern "C"
+
+namespace {
+
+// Shared by vattn_attn_prefill and vattn_attn_prefill_paged: work queues per XCD, index upload, launch.
+// The callers have validated the requests.
+int prefill_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
+                   const int32_t* cu_q, const int64_t* kv_lens, int n, float scale, const PagedKv* paged) {
     const int H = ctx->cfg.num_kv_heads, Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
     // 256 query rows per work item for both kernels; the wide one (four waves of 64 rows, software-pipelined)
     // is opt-in: measured slower.
-    const bool wide = ctx->prefill_wide;
+    const bool wide = ctx->prefill_wide && !paged;
     // Default kernel: twelve waves (384 rows per work item, three waves per SIMD) when that still leaves
     // every CU several work items, else eight waves (256 rows).
     int waves = 8;
@@ -337,12 +339,6 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
         if (items12 >= 4 * static_cast<int64_t>(ctx->num_cus)) waves = 12;
     }
     const int BM = wide ? 256 : 32 * waves;
-    for (int r = 0; r < n; ++r) {
-        const int64_t ql = static_cast<int64_t>(cu_q[r + 1]) - cu_q[r];
-        if (ql < 0) { set_error("attn_prefill: cu_q must be non-decreasing"); return -1; }
-        if (kv_lens[r] < ql) { set_error("attn_prefill: kv_len < q_len for batch slot " + std::to_string(r)); return -1; }
-        if (ql > 0 && !check_request(ctx, reqids[r], kv_lens[r], "attn_prefill")) return -1;
-    }
     // One queue per XCD.  Workgroup ids are dealt to the 8 XCDs round-robin, so giving XCD x the
     // streams (request, KV head, tile class) with index == x (mod 8) keeps all readers of one K/V
     // stream behind the same L2.  KV heads are split into tile classes when there are fewer than 8.
@@ -370,10 +366,14 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
     const size_t off_cu = sizeof(int32_t) * n;
     const size_t off_kv = off_cu + sizeof(int32_t) * (n + 1);
     const size_t off_items = align_up(off_kv + sizeof(int32_t) * n, 16);
-    const size_t bytes = off_items + sizeof(PrefillItem) * per_xcd * 8;
+    const size_t off_tab = align_up(off_items + sizeof(PrefillItem) * per_xcd * 8, 16);
+    const size_t tab_bytes = paged ? sizeof(int32_t) * static_cast<size_t>(n) * paged->table_stride : 0;
+    const size_t bytes = off_tab + tab_bytes;
     char *h, *d;
     if (!ctx->ring.acquire(bytes, &h, &d)) return -1;
-    std::memcpy(h, reqids, sizeof(int32_t) * n);
+    if (reqids) std::memcpy(h, reqids, sizeof(int32_t) * n);
+    else std::memset(h, 0, sizeof(int32_t) * n);
+    if (paged) std::memcpy(h + off_tab, paged->table, tab_bytes);
     std::memcpy(h + off_cu, cu_q, sizeof(int32_t) * (n + 1));
     int32_t* h_kv = reinterpret_cast<int32_t*>(h + off_kv);
     for (int r = 0; r < n; ++r) h_kv[r] = static_cast<int32_t>(kv_lens[r]);
@@ -386,8 +386,15 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
 
     PrefillArgs a{};
     a.q = q; a.o = o;
-    a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1); a.S = ctx->mem.S();
-    a.Hq = Hq; a.H = H; a.D = D; a.row_stride = static_cast<int>(ctx->mem.token_stride());
+    if (paged) {
+        a.k_base = static_cast<const char*>(paged->k_pool); a.v_base = static_cast<const char*>(paged->v_pool); a.S = 0;
+        a.row_stride = static_cast<int>(ctx->mem.T());
+        a.block_table = reinterpret_cast<const int32_t*>(d + off_tab); a.table_stride = paged->table_stride; a.block_tokens = paged->block_tokens;
+    } else {
+        a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1); a.S = ctx->mem.S();
+        a.row_stride = static_cast<int>(ctx->mem.token_stride());
+    }
+    a.Hq = Hq; a.H = H; a.D = D;
     a.reqids = reinterpret_cast<const int32_t*>(d);
     a.cu_q = reinterpret_cast<const int32_t*>(d + off_cu);
     a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
@@ -397,6 +404,51 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
     if (ctx->timing && !ctx->timers[1].next(&ev.start, &ev.stop)) return -1;
     if (!(wide ? launch_prefill_wide(a, s, ev) : launch_prefill(a, s, ev))) return -1;
     return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
+                       const int32_t* cu_q, const int64_t* kv_lens, int n, float scale) {
+    if (!check_ctx_layer(ctx, layer, "attn_prefill")) return -1;
+    if (n < 0 || (n > 0 && (!q || !o || !reqids || !cu_q || !kv_lens))) { set_error("attn_prefill: null argument"); return -1; }
+    if (n == 0) return 0;
+    if (cu_q[0] != 0) { set_error("attn_prefill: cu_q[0] must be 0"); return -1; }
+    for (int r = 0; r < n; ++r) {
+        const int64_t ql = static_cast<int64_t>(cu_q[r + 1]) - cu_q[r];
+        if (ql < 0) { set_error("attn_prefill: cu_q must be non-decreasing"); return -1; }
+        if (kv_lens[r] < ql) { set_error("attn_prefill: kv_len < q_len for batch slot " + std::to_string(r)); return -1; }
+        if (ql > 0 && !check_request(ctx, reqids[r], kv_lens[r], "attn_prefill")) return -1;
+    }
+    return prefill_common(ctx, layer, stream, q, o, reqids, cu_q, kv_lens, n, scale, nullptr);
+}
+
+int vattn_attn_prefill_paged(vattn_ctx* ctx, void* stream, const void* q, void* o, const void* k_pool, const void* v_pool,
+                             int64_t num_blocks, int block_tokens, const int32_t* block_table, int max_blocks_per_req,
+                             const int32_t* cu_q, const int64_t* kv_lens, int n, float scale) {
+    if (!ctx) { set_error("attn_prefill_paged: null context"); return -1; }
+    if (n < 0 || (n > 0 && (!q || !o || !k_pool || !v_pool || !block_table || !cu_q || !kv_lens))) { set_error("attn_prefill_paged: null argument"); return -1; }
+    if (n == 0) return 0;
+    if (cu_q[0] != 0) { set_error("attn_prefill_paged: cu_q[0] must be 0"); return -1; }
+    if (block_tokens < 64 || block_tokens % 64 != 0) { set_error("attn_prefill_paged: block_tokens must be a positive multiple of 64"); return -1; }
+    if (num_blocks <= 0 || num_blocks > INT32_MAX || max_blocks_per_req <= 0) { set_error("attn_prefill_paged: invalid pool or table size"); return -1; }
+    for (int r = 0; r < n; ++r) {
+        const int64_t ql = static_cast<int64_t>(cu_q[r + 1]) - cu_q[r];
+        if (ql < 0) { set_error("attn_prefill_paged: cu_q must be non-decreasing"); return -1; }
+        if (kv_lens[r] < ql || kv_lens[r] > static_cast<int64_t>(max_blocks_per_req) * block_tokens) {
+            set_error("attn_prefill_paged: context length of slot " + std::to_string(r) + " is below q_len or does not fit its block-table row");
+            return -1;
+        }
+        const int64_t used = (kv_lens[r] + block_tokens - 1) / block_tokens;
+        for (int64_t j = 0; j < used; ++j) {
+            const int32_t b = block_table[static_cast<int64_t>(r) * max_blocks_per_req + j];
+            if (b < 0 || b >= num_blocks) { set_error("attn_prefill_paged: block index out of range in slot " + std::to_string(r)); return -1; }
+        }
+    }
+    const PagedKv pk{k_pool, v_pool, num_blocks, block_tokens, block_table, max_blocks_per_req};
+    return prefill_common(ctx, 0, stream, q, o, nullptr, cu_q, kv_lens, n, scale, &pk);
 }
 
 int vattn_set_timing(vattn_ctx* ctx, int enabled) {

@@ -100,7 +100,9 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
     const int ntiles = (n_kv + kBN - 1) / kBN;
 
     const int rs32 = a.row_stride;             // bytes between consecutive tokens of this layer
-    const int64_t sub = static_cast<int64_t>(a.reqids[req]) * a.S + static_cast<int64_t>(it.kvh) * G::RB;
+    // contiguous KV: one base per request; paged comparison variant: only the head offset, the block comes per tile
+    const bool paged = a.block_table != nullptr;
+    const int64_t sub = (paged ? 0 : static_cast<int64_t>(a.reqids[req]) * a.S) + static_cast<int64_t>(it.kvh) * G::RB;
     const char* kp = a.k_base + sub;
     const char* vp = a.v_base + sub;
 
@@ -143,8 +145,12 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
     // instruction is issued between the first of these loads and the end of the loop.
     auto issue_loads = [&](int t) {
         const int tok = t * kBN;
-        const int64_t boff = static_cast<int64_t>(tok) * rs32;
         const int rows = min(kv_len - tok, kBN);   // <= 0 past the end: everything out of range
+        int64_t boff = static_cast<int64_t>(tok) * rs32;
+        if (paged && rows > 0) {   // block-table lookup; a tile never straddles a block (block_tokens is a multiple of the tile)
+            const int blk = a.block_table[static_cast<int64_t>(req) * a.table_stride + tok / a.block_tokens];
+            boff = (static_cast<int64_t>(blk) * a.block_tokens + tok % a.block_tokens) * rs32;
+        }
         const uint32_t nrec = rows > 0 ? static_cast<uint32_t>((rows - 1) * rs32 + G::RB) : 0u;
         const uint64_t ka = reinterpret_cast<uint64_t>(kp + boff), va = reinterpret_cast<uint64_t>(vp + boff);
         // raw buffer resource: base[47:0], stride 0, num_records, data format word

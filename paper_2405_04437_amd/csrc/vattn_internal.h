@@ -110,6 +110,9 @@ struct PrefillArgs {
     const PrefillItem* items;               // device: 8 queues of items_per_xcd entries each
     int items_per_xcd; int n;
     int waves;                              // default kernel: waves per workgroup (8 or 12); a work item is 32*waves rows
+    // Paged comparison variant only (default kernel): k_base / v_base are block pools [num_blocks, block_tokens,
+    // H, D]; block_table[req * table_stride + j] names the block with tokens j*block_tokens .. of batch slot req.
+    const int32_t* block_table; int table_stride; int block_tokens;
     float scale;
 };
 // Two kernels: the default with 32 query rows per wave and `waves` = 8 or 12 waves per work item, and a

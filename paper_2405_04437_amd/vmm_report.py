@@ -148,6 +148,53 @@ def paged_overhead(P, torch, W, quick):
         del pool_k, pool_v
     s.close()
     print()
+    print("Prefill (Llama-3-8B shape, one 16384-token prompt), same kernel with and without the block-table lookup:\n")
+    print("| KV layout | prefill kernel ms | TFLOP/s (causal flops) |")
+    print("|---|---|---|")
+    from paper_2405_04437_amd.runtime import KvSession
+
+    shape = W.LLAMA3_8B
+    L = 16384
+    flops = 4 * shape.num_q_heads * shape.head_dim * (L * (L + 1) // 2)
+    G = 2 * MiB
+    per = (L * shape.token_bytes + G - 1) // G * G
+    s = KvSession(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, 1, L, per * 2, 1, G)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(2)
+    rid = s.admit(L); s.step()
+    kv = torch.randn((L, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    s.append(0, kv, kv, [rid], [0, L], [0])
+    q = torch.randn((L, shape.num_q_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    o = torch.empty_like(q)
+    scale = W.softmax_scale(shape.head_dim)
+
+    def timed_p(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        s.va.set_timing(True); s.va.kernel_time(1)
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        ms, cnt = s.va.kernel_time(1)
+        s.va.set_timing(False)
+        return ms / cnt
+
+    ms = timed_p(lambda: s.prefill(0, q, [rid], [0, L], [L], scale, out=o))
+    print(f"| contiguous (virtual tensor) | {ms:.3f} | {flops / ms / 1e9:.0f} |")
+    stream = s.stream
+    for bt in (64, 256, 2048):
+        nb = L // bt
+        pool = kv.reshape(nb, bt, shape.num_kv_heads, shape.head_dim)
+        perm = rng.permutation(nb)
+        shuffled = torch.empty_like(pool)
+        shuffled[torch.from_numpy(perm).cuda()] = pool          # logical block j lives in pool slot perm[j]
+        table = perm.astype(np.int32).reshape(1, nb)
+        ms = timed_p(lambda: s.va.attn_prefill_paged(stream, q, o, shuffled, shuffled, nb, bt, table, [0, L], [L], scale))
+        print(f"| paged, {bt}-token blocks | {ms:.3f} | {flops / ms / 1e9:.0f} |")
+    ms = timed_p(lambda: s.prefill(0, q, [rid], [0, L], [L], scale, out=o))
+    print(f"| contiguous, measured again at the end | {ms:.3f} | {flops / ms / 1e9:.0f} |")
+    s.close()
+    print()
 
 
 def slicing_effect(P, torch, W, quick):

@@ -186,3 +186,46 @@ def test_paged_comparison_kernel_matches_oracle(block_tokens, Hq, H, D):
     assert s.va.attn_decode_paged(s.stream, q, o, kp, vp, num_blocks, block_tokens, table, long, scale, ws, ws.numel()) == -1
     assert s.va.attn_decode_paged(s.stream, q, o, kp, vp, num_blocks, 48, table, kv_lens, scale, ws, ws.numel()) == -1
     s.close()
+
+
+@pytest.mark.parametrize("block_tokens", [64, 256])
+@pytest.mark.parametrize("Hq,H,D", [(32, 8, 128), (14, 2, 64)])
+def test_paged_prefill_comparison_kernel_matches_oracle(block_tokens, Hq, H, D):
+    """The prefill kernel with a block-table lookup per tile (comparison variant) over a shuffled block pool:
+    whole prompts and a chunk appended to an existing context."""
+    import torch
+    import paper_2405_04437_amd as P
+    from paper_2405_04437_amd.runtime import KvSession, bits_to_tensor, tensor_to_f32
+
+    shape = W.Shape("t", Hq, H, D, 1)
+    q_lens = [1, 65, 700, 300]
+    kv_lens = [1, 65, 700, 1500]
+    n = len(kv_lens)
+    inp = W.draw_attention_inputs(shape, q_lens, kv_lens, seed=block_tokens + Hq)
+    scale = W.softmax_scale(D)
+    blocks_per = [(L + block_tokens - 1) // block_tokens for L in kv_lens]
+    max_blocks, num_blocks = max(blocks_per), sum(blocks_per) + 3
+    ids = np.random.default_rng(11).permutation(num_blocks)
+    table = np.full((n, max_blocks), -1, dtype=np.int32)
+    kpool = np.zeros((num_blocks, block_tokens, H, D), dtype=np.uint16)
+    vpool = np.zeros_like(kpool)
+    nxt = 0
+    for r, L in enumerate(kv_lens):
+        for j in range(blocks_per[r]):
+            b = int(ids[nxt]); nxt += 1
+            table[r, j] = b
+            a, e = j * block_tokens, min(L, (j + 1) * block_tokens)
+            kpool[b, :e - a] = inp.k[r][a:e]
+            vpool[b, :e - a] = inp.v[r][a:e]
+    s = KvSession(Hq, H, D, 2, 64, 0, 1, 2 * MiB)
+    q = bits_to_tensor(inp.q)
+    o = torch.empty_like(q)
+    kp, vp = bits_to_tensor(kpool), bits_to_tensor(vpool)
+    rc = s.va.attn_prefill_paged(s.stream, q, o, kp, vp, num_blocks, block_tokens, table, inp.cu_q, kv_lens, scale)
+    assert rc == 0, P.last_error()
+    want = OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale)
+    check(tensor_to_f32(o), want, f"paged prefill block={block_tokens}")
+    bad = table.copy(); bad[2, 0] = -1
+    assert s.va.attn_prefill_paged(s.stream, q, o, kp, vp, num_blocks, block_tokens, bad, inp.cu_q, kv_lens, scale) == -1
+    assert s.va.attn_prefill_paged(s.stream, q, o, kp, vp, num_blocks, 32, table, inp.cu_q, kv_lens, scale) == -1
+    s.close()
