@@ -12,7 +12,8 @@
   4. deferred reclamation + eager allocation: time from "request arrives" to "prefill may start"
      (alloc_reqid + step) with pages unmapped on free, deferred, and deferred + eager;
   5. the decode kernel over contiguous KV vs its paged comparison variant (block table inside the kernel);
-  6. the decode kernel over the all-layers-in-one-buffer layout (tensor slicing, strided tokens).
+  6. the decode kernel over the all-layers-in-one-buffer layout (tensor slicing, strided tokens);
+  7. internal fragmentation per page-group size and layout.
 
 Everything runs through the C ABI (paper_2405_04437_amd.binding); no result is checked here - parity lives in
 tests/.  Usage: python paper_2405_04437_amd/vmm_report.py [--quick]
@@ -242,6 +243,37 @@ def slicing_effect(P, torch, W, quick):
     print()
 
 
+def fragmentation(P, W, quick):
+    print("## 7. Internal fragmentation: physical memory mapped vs KV bytes in use\n")
+    print("32 requests with the context lengths of the Yi-6B decode workload (U[1024,16384]), 2 layers; what step() has")
+    print("mapped once every request is backed.  One buffer for all layers (tensor slicing) divides the waste per")
+    print("request by the number of layers.\n")
+    print("| layout | page-group | tokens per page-group | mapped MiB | in use MiB | wasted | wasted per request KiB |")
+    print("|---|---|---|---|---|---|---|")
+    from paper_2405_04437_amd.binding import Vattn
+
+    shape = W.YI_6B
+    wl = W.config(1)
+    lens = [int(x) for x in wl.kv_lens[:32]]
+    N, B = 2, 32
+    in_use = sum(lens) * shape.token_bytes * 2 * N
+    for name, G, flags in (("per-layer buffers", 64 * KiB, 0), ("per-layer buffers", 256 * KiB, 0), ("per-layer buffers", 2 * MiB, 0),
+                           ("one buffer for all layers", 2 * MiB, P.FLAG_TENSOR_SLICING)):
+        tok = shape.token_bytes * (N if flags else 1)
+        per_req = (16384 * tok + G - 1) // G * G
+        va = Vattn(N, B, 16384, shape.num_q_heads, shape.num_kv_heads, shape.head_dim, per_req * (2 if flags else 2 * N) * B, G,
+                   flags=flags)
+        seq = np.zeros(B, dtype=np.int64)
+        for L in lens:
+            seq[va.alloc_reqid()] = L
+        assert va.step(seq) == 0
+        Gb, S, total, free = va.stats()
+        mapped = (total - free) * Gb
+        print(f"| {name} | {G // KiB} KiB | {G // tok} | {mapped / MiB:.1f} | {in_use / MiB:.1f} | {100 * (mapped - in_use) / mapped:.1f} % | {(mapped - in_use) / B / KiB:.0f} |")
+        va.destroy()
+    print()
+
+
 def latency_hiding(P, torch, W, quick):
     print("## 3. Synchronous step() vs background look-ahead (decode loop, 32 requests, 256 KiB page-groups)\n")
     print("Every request crosses a page-group boundary every 256 tokens; the 32 requests start at staggered offsets, so")
@@ -357,6 +389,7 @@ def main() -> int:
     prefill_admission(P, torch, W, args.quick)
     paged_overhead(P, torch, W, args.quick)
     slicing_effect(P, torch, W, args.quick)
+    fragmentation(P, W, args.quick)
     return 0
 
 
