@@ -2,13 +2,16 @@
 """Benchmark of the contiguous-KV attention hot path on one MI355X.
 
 Headline workload (N=1): BASELINE config 2, "Yi-6B-shaped decode" - 64 requests, 32 query heads,
-4 KV heads, head_dim 128, bf16, contexts U[1024,16384]; every step each request grows by one token:
-    step()  ->  append_kv (new K/V rows, all layers; fused into the decode kernel for the attended layer)
-            ->  attn_decode (split-K + reduce) on one layer
-i.e. one pass over all rows of the hot path.  Layers are rotated so consecutive steps read different
-KV buffers.  `value` is algorithmic KV bytes moved per second over the whole step (inputs resident in
-HBM); `roofline` prices the dominant kernel (split-K decode) alone, timed with HIP events the library
-records around every launch on the launch stream.
+4 KV heads, head_dim 128, bf16, contexts U[1024,16384], 32 decoder layers (44 GB of KV).  A step is one
+serving iteration of Algorithm 1 in which every request grows by one token:
+    step()  ->  for each of the 32 layers: attn_decode_append (the new K/V row is written by the
+                split-K kernel that reads the cache, then the reduce kernel)  ->  stream synchronise
+i.e. one pass over all rows of the hot path at the model's depth.  The KV grows on the library's helper
+thread with a 64-token look-ahead (Sec. 6.1); --sync-maps maps inside step() instead.  `value` is
+algorithmic KV bytes moved per second over the whole step (inputs resident in HBM); `roofline` prices
+the dominant kernel (split-K decode) alone, timed with HIP events the library records around every
+launch on the launch stream.  `also.C2_one_layer_per_sync` is the same batch with a host synchronisation
+after each single layer, which exposes the per-iteration host work instead of amortising it.
 
 The line also carries `also`: prefill (config 3) TFLOP/s, the mixed step of config 4 and the
 long-context request of config 5, each with its own roofline fraction, and `cpu_baseline`: the CPU
@@ -73,22 +76,31 @@ def _fill_contexts(sess, torch, gen, shape, kv_lens, layers, keep_host=False):
     return ids, host
 
 
-def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, churn=False):
-    from paper_2405_04437_amd import POLICY_DEFERRED
+def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, churn=False, whole_model=False,
+               background=False):
+    """Decode steps.  whole_model=False: one layer's attention per step (the layer rotates) and a stream
+    synchronisation after it.  whole_model=True: a serving iteration - step() once, then the fused
+    append + attention of every one of `layers` layers, then the synchronisation (Algorithm 1)."""
+    from paper_2405_04437_amd import FLAG_BACKGROUND, POLICY_DEFERRED
     from paper_2405_04437_amd.runtime import KvSession, tensor_to_bits, tensor_to_f32
 
     shape = wl.shape
     n = sum(1 for q in wl.q_lens if q == 1)
     kv_lens = [int(x) for x in wl.kv_lens[:n]]
-    total_steps = 2 * steps + warmup + 2
+    ksteps = max(1, steps // 8) if whole_model else steps     # steps of the second, event-timed pass
+    total_steps = steps + ksteps + warmup + 2
     ctx_hi = wl.extra["ctx_range"][1] if churn else 0
     max_ctx = max(max(kv_lens), ctx_hi) + total_steps + 8
     G = 2 * MiB
     headroom = n // 4 + 4
     per_req = (max_ctx * shape.token_bytes + G - 1) // G * G
     budget = per_req * 2 * layers * (n + headroom)
+    if not churn:   # the page-groups these requests can reach by the last step, and a few spare rows
+        rows = sum((int(L + total_steps + 8) * shape.token_bytes + G - 1) // G for L in kv_lens) + 8
+        budget = rows * G * 2 * layers
     sess = KvSession(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, n + headroom, max_ctx, budget, layers, G,
-                     POLICY_DEFERRED)
+                     POLICY_DEFERRED, flags=FLAG_BACKGROUND if background else 0,
+                     lookahead_tokens=64 if background else 0)
     gen = torch.Generator(device="cuda"); gen.manual_seed(wl.seed)
     ids, host = _fill_contexts(sess, torch, gen, shape, kv_lens, layers, keep_host=with_oracle)
     for r, L in zip(ids, kv_lens):
@@ -131,18 +143,24 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
                     assert va.append_kv(layer, stream, kbig[:L], vbig[:L], ids[slot:slot + 1], [0, L], [0]) == 0
         seq[ids] = lens + 1
         assert va.step(seq) == 0
-        att = i % layers                  # the layer attended to in this step; its append rides in the decode kernel
-        assert va.attn_decode_append(att, stream, q, knew, vnew, o, ids, lens + 1, scale, ws, ws.numel()) == 0
-        for layer in range(layers):       # the other layers' appends are independent of it and queue up behind
-            if layer != att:
-                assert va.append_kv(layer, stream, knew, vnew, ids, cu, lens) == 0
+        if whole_model:                   # every layer: the new K/V row rides in that layer's decode kernel
+            for layer in range(layers):
+                assert va.attn_decode_append(layer, stream, q, knew, vnew, o, ids, lens + 1, scale, ws, ws.numel()) == 0
+        else:
+            att = i % layers              # the layer attended to in this step; its append rides in the decode kernel
+            assert va.attn_decode_append(att, stream, q, knew, vnew, o, ids, lens + 1, scale, ws, ws.numel()) == 0
+            for layer in range(layers):   # the other layers' appends are independent of it and queue up behind
+                if layer != att:
+                    assert va.append_kv(layer, stream, knew, vnew, ids, cu, lens) == 0
         lens[:] += 1
         # iteration boundary of the serving loop (Algorithm 1): the framework needs this iteration's
         # output on the host before it can schedule the next one
         torch_stream.synchronize()
 
+    launches_per_step = layers if whole_model else 1
+
     def step_bytes():
-        return int(lens.sum()) * per_tok + qo_bytes
+        return (int(lens.sum()) * per_tok + qo_bytes) * launches_per_step
 
     for i in range(warmup):
         one_step(i)
@@ -162,7 +180,6 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
     sess.va.set_timing(True)
     sess.va.kernel_time(0); sess.va.kernel_time(2)
     kbytes = 0
-    ksteps = steps
     for i in range(ksteps):
         one_step(warmup + steps + i)
         kbytes += step_bytes()
@@ -182,6 +199,7 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
         "bytes_per_step": bytes_per_step,
         "kbytes_per_launch": kbytes_per_launch,
         "tokens_in_batch": int(lens.sum()),
+        "layers": layers, "decode_launches_per_step": launches_per_step,
         "map_calls_in_timed_region": map1[0] - map0[0],
         "map_us_in_timed_region": map1[2] - map0[2],
         "unmap_calls_in_timed_region": map1[1] - map0[1],
@@ -191,7 +209,7 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
         import numpy as np
         from oracle import attention as OA
 
-        last_layer = (warmup + 2 * steps - 1) % layers
+        last_layer = layers - 1 if whole_model else (warmup + steps + ksteps - 1) % layers
         torch.cuda.synchronize()
         qb = tensor_to_bits(q)
         kb_new, vb_new = tensor_to_bits(knew), tensor_to_bits(vnew)
@@ -210,7 +228,7 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
         err = float(np.abs(got - want).max())
         rel = float((np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max())
         res["cpu_baseline"] = {
-            "value": step_bytes() / dt / 1e9, "unit": "GB/s", "cores": OA.num_threads(), "kind": "oracle",
+            "value": step_bytes() / launches_per_step / dt / 1e9, "unit": "GB/s", "cores": OA.num_threads(), "kind": "oracle",
             "sample": f"the full decode batch of the last timed step ({n} requests, {int(lens.sum())} tokens, layer {last_layer}), {reps} times: {dt:.2f} s each",
             "gpu_vs_oracle_max_abs": err, "gpu_vs_oracle_row_rel": rel,
         }
@@ -272,12 +290,15 @@ def _measured_traffic(name):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=300,
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20,
                     help="untimed steps; the first ~50 ms of sustained load on a fresh process contain a one-off "
-                         "30-40 ms device stall (seen between two back-to-back launches), so keep this >= 200")
+                         "30-40 ms device stall (seen between two back-to-back launches), so keep this >= 10 "
+                         "whole-model steps")
     ap.add_argument("--only", choices=["all", "decode", "prefill", "copy"], default="all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="decoder layers per decode step (0 = the model's depth)")
+    ap.add_argument("--sync-maps", action="store_true", help="grow the KV inside step() instead of on the helper thread")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards by request / KV head with no exchange "
@@ -297,7 +318,7 @@ def main() -> int:
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "C2 Yi-6B-shaped decode: 64 requests, Hq=32 H=4 D=128, ctx U[1024,16384], "
-                                  "one token per request per step (step + append_kv on both layers, fused into the decode kernel for the attended one, + split-K decode + reduce), 2 MiB page-groups"}}
+                                  "one token per request per step (step() + per layer: K/V append fused into split-K decode, + reduce), 2 MiB page-groups"}}
     also = {}
     if args.only == "copy":
         # Calibration for the HBM-traffic counters: a plain device copy of known size (1 GiB read + 1 GiB
@@ -312,7 +333,11 @@ def main() -> int:
         return 0
     if args.only in ("all", "decode"):
         wl = W.config(1)
-        r = run_decode(args, torch, W, wl, args.steps, args.warmup, with_oracle=not args.no_cpu_baseline)
+        depth = args.layers or wl.shape.num_layers
+        r = run_decode(args, torch, W, wl, args.steps, args.warmup, layers=depth, with_oracle=not args.no_cpu_baseline,
+                       whole_model=True, background=not args.sync_maps)
+        out["config"].update({"layers": depth, "decode_launches_per_step": depth,
+                              "kv_growth": "step() on the caller's thread" if args.sync_maps else "helper thread, 64-token look-ahead"})
         out["value"] = r["gbs_step"]
         out["ms_per_step"] = r["ms_per_step"]
         out["pct_of_hbm_peak"] = 100.0 * r["gbs_step"] / HBM_PEAK_GBS
@@ -326,6 +351,12 @@ def main() -> int:
             out["cpu_baseline"] = r.pop("cpu_baseline")
         out["decode_detail"] = {k: r[k] for k in ("reduce_ms", "tokens_in_batch", "map_calls_in_timed_region",
                                                   "map_us_in_timed_region", "unmap_calls_in_timed_region")}
+        if args.only == "all":
+            # the same batch with a host synchronisation after every single layer's attention: the
+            # cost of the per-iteration host work when nothing amortises it
+            r1 = run_decode(args, torch, W, wl, 400, 300, layers=2, with_oracle=False)
+            also["C2_one_layer_per_sync"] = {"gbs_step": r1["gbs_step"], "ms_per_step": r1["ms_per_step"],
+                                             "gbs_kernel": r1["gbs_kernel"], "kernel_ms": r1["kernel_ms"]}
     if args.only in ("all", "prefill"):
         wl3 = W.config(2)
         p = run_prefill(args, torch, W, wl3, iters=3, warmup=1)
