@@ -202,6 +202,17 @@ int vattn_attn_decode_append(vattn_ctx* ctx, int layer, void* stream, const void
                              const int32_t* reqids /*host*/, const int64_t* kv_lens /*host*/, int n, float scale,
                              void* workspace /*device*/, size_t workspace_bytes);
 
+/* Prefill with the KV append fused in (the second half of the "fused append" the paper's Sec. 7.1 leaves as
+ * a separate copy).  k_new, v_new: [sum q_len, H, D] bf16 (device), the K/V rows of the query tokens, packed
+ * like q; they are NOT in the cache yet.  kv_lens[r] counts them (positions kv_lens[r]-q_len .. kv_lens[r]-1,
+ * which step() must already have mapped).  One launch stores the rows into the cache of `layer` and attends;
+ * the result equals vattn_append_kv (kv_len_before = kv_lens - q_len) followed by vattn_attn_prefill.  A reqId
+ * with a non-empty chunk may appear only once.  Not available with VATTN_FLAG_TENSOR_SLICING (returns -1). */
+int vattn_attn_prefill_append(vattn_ctx* ctx, int layer, void* stream, const void* q /*device*/,
+                              const void* k_new /*device*/, const void* v_new /*device*/, void* o /*device*/,
+                              const int32_t* reqids /*host*/, const int32_t* cu_q /*host*/,
+                              const int64_t* kv_lens /*host*/, int n, float scale);
+
 /* Comparison kernel, not part of the method: the SAME split-K decode over a PAGED KV cache, the design
  * the paper argues against (Sec. 3: block table inside the kernel), to re-measure on this GPU what the
  * indirection costs.  k_pool, v_pool: caller-owned device pools [num_blocks, block_tokens, H, D] bf16;

@@ -62,6 +62,7 @@ def _load() -> ctypes.CDLL:
                                       ctypes.c_size_t]
     lib.vattn_attn_decode_append.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, i32p, i64p, ctypes.c_int, ctypes.c_float, vp,
                                              ctypes.c_size_t]
+    lib.vattn_attn_prefill_append.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, i32p, i32p, i64p, ctypes.c_int, ctypes.c_float]
     lib.vattn_attn_decode_paged.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, i32p, ctypes.c_int, i64p,
                                             ctypes.c_int, ctypes.c_float, vp, ctypes.c_size_t]
     lib.vattn_attn_prefill_paged.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, i32p, ctypes.c_int, i32p, i64p,
@@ -77,7 +78,8 @@ def _load() -> ctypes.CDLL:
     for name in ("vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_query",
                  "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill", "vattn_attn_decode",
                  "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide",
-                 "vattn_step_counters", "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged"):
+                 "vattn_step_counters", "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
+                 "vattn_attn_prefill_append"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -88,7 +90,8 @@ EXPORTED = ["vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqi
             "vattn_query", "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill",
             "vattn_decode_workspace_bytes", "vattn_attn_decode", "vattn_set_timing", "vattn_kernel_time",
             "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide", "vattn_step_counters",
-            "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged", "vattn_last_error"]
+            "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
+            "vattn_attn_prefill_append", "vattn_last_error"]
 
 
 def last_error() -> str:
@@ -216,6 +219,13 @@ class Vattn:
         k, kp = _i64(kv_lens)
         return lib.vattn_attn_decode_append(self._h, layer, stream, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(o), rp, kp,
                                             len(r), scale, _ptr(workspace), workspace_bytes)
+
+    def attn_prefill_append(self, layer: int, stream: int, q, k_new, v_new, o, reqids, cu_q, kv_lens, scale: float) -> int:
+        r, rp = _i32(reqids)
+        c, cp = _i32(cu_q)
+        k, kp = _i64(kv_lens)
+        return lib.vattn_attn_prefill_append(self._h, layer, stream, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(o), rp, cp, kp,
+                                             len(r), scale)
 
     def attn_decode_paged(self, stream: int, q, o, k_pool, v_pool, num_blocks: int, block_tokens: int, block_table,
                           kv_lens, scale: float, workspace, workspace_bytes: int) -> int:

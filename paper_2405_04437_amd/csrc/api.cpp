@@ -325,11 +325,11 @@ namespace {
 // Shared by vattn_attn_prefill and vattn_attn_prefill_paged: work queues per XCD, index upload, launch.
 // The callers have validated the requests.
 int prefill_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
-                   const int32_t* cu_q, const int64_t* kv_lens, int n, float scale, const PagedKv* paged) {
+                   const int32_t* cu_q, const int64_t* kv_lens, int n, float scale, const PagedKv* paged, const NewRows* fresh = nullptr) {
     const int H = ctx->cfg.num_kv_heads, Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
     // 256 query rows per work item for both kernels; the wide one (four waves of 64 rows, software-pipelined)
     // is opt-in: measured slower.
-    const bool wide = ctx->prefill_wide && !paged;
+    const bool wide = ctx->prefill_wide && !paged && !fresh;
     // Default kernel: twelve waves (384 rows per work item, three waves per SIMD) when that still leaves
     // every CU several work items, else eight waves (256 rows).
     int waves = 8;
@@ -400,6 +400,7 @@ int prefill_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void*
     a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
     a.items = reinterpret_cast<const PrefillItem*>(d + off_items);
     a.items_per_xcd = static_cast<int>(per_xcd); a.n = n; a.scale = scale; a.waves = waves;
+    if (fresh) { a.k_new = fresh->k_new; a.v_new = fresh->v_new; }
     LaunchEvents ev;
     if (ctx->timing && !ctx->timers[1].next(&ev.start, &ev.stop)) return -1;
     if (!(wide ? launch_prefill_wide(a, s, ev) : launch_prefill(a, s, ev))) return -1;
@@ -423,6 +424,25 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
         if (ql > 0 && !check_request(ctx, reqids[r], kv_lens[r], "attn_prefill")) return -1;
     }
     return prefill_common(ctx, layer, stream, q, o, reqids, cu_q, kv_lens, n, scale, nullptr);
+}
+
+int vattn_attn_prefill_append(vattn_ctx* ctx, int layer, void* stream, const void* q, const void* k_new, const void* v_new, void* o,
+                              const int32_t* reqids, const int32_t* cu_q, const int64_t* kv_lens, int n, float scale) {
+    if (!check_ctx_layer(ctx, layer, "attn_prefill_append")) return -1;
+    if (n < 0 || (n > 0 && (!q || !k_new || !v_new || !o || !reqids || !cu_q || !kv_lens))) { set_error("attn_prefill_append: null argument"); return -1; }
+    if (n == 0) return 0;
+    if (ctx->mem.token_stride() != ctx->mem.T()) { set_error("attn_prefill_append: not available with the tensor-slicing layout"); return -1; }
+    if (cu_q[0] != 0) { set_error("attn_prefill_append: cu_q[0] must be 0"); return -1; }
+    for (int r = 0; r < n; ++r) {
+        const int64_t ql = static_cast<int64_t>(cu_q[r + 1]) - cu_q[r];
+        if (ql < 0) { set_error("attn_prefill_append: cu_q must be non-decreasing"); return -1; }
+        if (kv_lens[r] < ql) { set_error("attn_prefill_append: kv_len < q_len for batch slot " + std::to_string(r)); return -1; }
+        if (ql > 0 && !check_request(ctx, reqids[r], kv_lens[r], "attn_prefill_append")) return -1;
+        for (int p = 0; ql > 0 && p < r; ++p)
+            if (reqids[p] == reqids[r] && cu_q[p + 1] > cu_q[p]) { set_error("attn_prefill_append: a reqId appears twice in the batch"); return -1; }
+    }
+    const NewRows fresh{k_new, v_new};
+    return prefill_common(ctx, layer, stream, q, o, reqids, cu_q, kv_lens, n, scale, nullptr, &fresh);
 }
 
 int vattn_attn_prefill_paged(vattn_ctx* ctx, void* stream, const void* q, void* o, const void* k_pool, const void* v_pool,

@@ -18,6 +18,8 @@
 //    the host builds one work queue per XCD and gives each XCD whole (request, KV head) streams; the
 //    query heads of a group and neighbouring query tiles then run on the same XCD at the same time
 //    and share the K/V stream through that XCD's L2.
+//  * Optional fused KV append (template flag FUSED): the chunk's own K/V rows are read from the caller's
+//    arrays and stored into the cache by the same launch (what Sec. 7.1 of the paper does with a copy).
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
@@ -68,7 +70,11 @@ template <int D, int NW> struct PGeo {
 
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
-template <int D, int NW>
+// FUSED: the K/V rows of the query tokens arrive in a.k_new / a.v_new and are not in the cache yet.  Tiles at or
+// beyond position kv_len - q_len are read from those arrays (same row stride as the cache), and the first
+// query head of every group stores the rows of its query tile into the cache; no workgroup ever reads a cache
+// row that this launch writes.
+template <int D, int NW, bool FUSED>
 __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a) {
     using G = PGeo<D, NW>;
     constexpr int kWaves = NW;
@@ -105,6 +111,26 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
     const int64_t sub = (paged ? 0 : static_cast<int64_t>(a.reqids[req]) * a.S) + static_cast<int64_t>(it.kvh) * G::RB;
     const char* kp = a.k_base + sub;
     const char* vp = a.v_base + sub;
+    const char* kn = nullptr;
+    const char* vn = nullptr;
+    if constexpr (FUSED) {
+        // row j of the request's new rows is position off + j of its context
+        const int64_t nsub = (static_cast<int64_t>(q_begin) * a.H + it.kvh) * G::RB;
+        kn = static_cast<const char*>(a.k_new) + nsub;
+        vn = static_cast<const char*>(a.v_new) + nsub;
+        if (slot % group == 0) {   // one query head per (request, KV head, query tile) stores that tile's rows
+            const int nrows = min(q0 + BM, q_len) - q0;
+            for (int i = tid; i < nrows * G::CH; i += NW * 64) {
+                const int row = q0 + i / G::CH, c = (i % G::CH) * 16;
+                const int64_t src = static_cast<int64_t>(row) * rs32 + c;
+                const int64_t dst = static_cast<int64_t>(off + row) * rs32 + c;
+                const u32x4 kx = *reinterpret_cast<const u32x4*>(kn + src);
+                const u32x4 vx = *reinterpret_cast<const u32x4*>(vn + src);
+                *reinterpret_cast<u32x4*>(const_cast<char*>(kp) + dst) = kx;
+                *reinterpret_cast<u32x4*>(const_cast<char*>(vp) + dst) = vx;
+            }
+        }
+    }
 
     // Q^T as B operand: lane (n = l%32, h = l/32) holds Q[row n][ks*16 + h*8 .. +8]
     const int row_lo = q0 + w * WR;               // first query row of this wave
@@ -143,10 +169,19 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
     // does not make the LDS reads of tile t wait for the loads of tile t+1 (it cannot tell the two stages
     // apart); the waits that are needed are placed by hand before the barriers.  No other vector-memory
     // instruction is issued between the first of these loads and the end of the loop.
+    const char* const kp_cache = kp;
+    const char* const vp_cache = vp;
     auto issue_loads = [&](int t) {
         const int tok = t * kBN;
         const int rows = min(kv_len - tok, kBN);   // <= 0 past the end: everything out of range
         int64_t boff = static_cast<int64_t>(tok) * rs32;
+        const char* kp = kp_cache;
+        const char* vp = vp_cache;
+        bool straddle = false;   // cache rows up to position off - 1, new rows from there on, in one tile
+        if constexpr (FUSED) {
+            if (tok >= off) { kp = kn; vp = vn; boff = static_cast<int64_t>(tok - off) * rs32; }   // a tile of new rows
+            else straddle = tok + kBN > off;
+        }
         if (paged && rows > 0) {   // block-table lookup; a tile never straddles a block (block_tokens is a multiple of the tile)
             const int blk = a.block_table[static_cast<int64_t>(req) * a.table_stride + tok / a.block_tokens];
             boff = (static_cast<int64_t>(blk) * a.block_tokens + tok % a.block_tokens) * rs32;
@@ -162,6 +197,30 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
             const int b = w + j * kWaves;                 // scalar: which 1 KiB block of the tile
             if (b < G::NB) {
                 const int so = b * G::RPW * rs32;
+                if constexpr (FUSED) {
+                    if (straddle) {
+                        // At most once per work item, and only when `off` is not a multiple of the tile.  Lanes whose
+                        // row lies below `off` load from the cache, the others from the new rows (a resource whose
+                        // row 0 is position `tok`, so the same offsets apply); a lane that is switched off writes
+                        // nothing to LDS (checked on the chip), so the two loads fill disjoint parts of the block.
+                        const uint64_t nka = reinterpret_cast<uint64_t>(kn) + static_cast<int64_t>(tok - off) * rs32;
+                        const uint64_t nva = reinterpret_cast<uint64_t>(vn) + static_cast<int64_t>(tok - off) * rs32;
+                        const u32x4 nkrs = {static_cast<uint32_t>(nka), static_cast<uint32_t>(nka >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
+                        const u32x4 nvrs = {static_cast<uint32_t>(nva), static_cast<uint32_t>(nva >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
+                        if (tok + b * G::RPW + dma_row < off) {
+                            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                                         :: "s"(kb + b * 1024), "v"(dma_voff_k[((j * kWaves) % PB) / STEP]), "s"(krs), "s"(so) : "memory", "m0");
+                            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                                         :: "s"(kb + G::KV + b * 1024), "v"(dma_voff_v), "s"(vrs), "s"(so) : "memory", "m0");
+                        } else {
+                            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                                         :: "s"(kb + b * 1024), "v"(dma_voff_k[((j * kWaves) % PB) / STEP]), "s"(nkrs), "s"(so) : "memory", "m0");
+                            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                                         :: "s"(kb + G::KV + b * 1024), "v"(dma_voff_v), "s"(nvrs), "s"(so) : "memory", "m0");
+                        }
+                        continue;
+                    }
+                }
                 asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                              :: "s"(kb + b * 1024), "v"(dma_voff_k[((j * kWaves) % PB) / STEP]), "s"(krs), "s"(so) : "memory", "m0");
                 asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
@@ -352,7 +411,7 @@ bool launch_prefill(const PrefillArgs& a_in, hipStream_t stream, LaunchEvents ev
     dim3 grid(static_cast<unsigned>(8 * a_in.items_per_xcd * group));
     if (grid.x == 0) return true;
     const PrefillArgs& a = a_in;
-    static bool allowed[4] = {};  // per kernel variant
+    static bool allowed[8] = {};  // per kernel variant
     auto launch = [&](auto kernel, int lds, int variant) -> bool {
         if (!allowed[variant]) {  // dynamic LDS above 64 KiB has to be allowed once per kernel
             if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds), "hipFuncSetAttribute")) return false;
@@ -362,8 +421,11 @@ bool launch_prefill(const PrefillArgs& a_in, hipStream_t stream, LaunchEvents ev
         return true;
     };
     bool ok;
-    if (a.waves == 12) ok = a.D == 128 ? launch(prefill_kernel<128, 12>, PGeo<128, 12>::LDS, 2) : launch(prefill_kernel<64, 12>, PGeo<64, 12>::LDS, 3);
-    else ok = a.D == 128 ? launch(prefill_kernel<128, 8>, PGeo<128, 8>::LDS, 0) : launch(prefill_kernel<64, 8>, PGeo<64, 8>::LDS, 1);
+    if (a.k_new) {
+        if (a.waves == 12) ok = a.D == 128 ? launch(prefill_kernel<128, 12, true>, PGeo<128, 12>::LDS, 6) : launch(prefill_kernel<64, 12, true>, PGeo<64, 12>::LDS, 7);
+        else ok = a.D == 128 ? launch(prefill_kernel<128, 8, true>, PGeo<128, 8>::LDS, 4) : launch(prefill_kernel<64, 8, true>, PGeo<64, 8>::LDS, 5);
+    } else if (a.waves == 12) ok = a.D == 128 ? launch(prefill_kernel<128, 12, false>, PGeo<128, 12>::LDS, 2) : launch(prefill_kernel<64, 12, false>, PGeo<64, 12>::LDS, 3);
+    else ok = a.D == 128 ? launch(prefill_kernel<128, 8, false>, PGeo<128, 8>::LDS, 0) : launch(prefill_kernel<64, 8, false>, PGeo<64, 8>::LDS, 1);
     if (!ok) return false;
     return hip_ok(hipGetLastError(), "prefill launch");
 }

@@ -114,6 +114,9 @@ struct PrefillArgs {
     // H, D]; block_table[req * table_stride + j] names the block with tokens j*block_tokens .. of batch slot req.
     const int32_t* block_table; int table_stride; int block_tokens;
     float scale;
+    // Fused append only (default kernel, unsliced layout): K/V rows [sum q_len, H, D] of the query tokens, which the
+    // kernel stores at positions kv_len - q_len .. kv_len - 1 and reads from here instead of from the cache (else null).
+    const void* k_new; const void* v_new;
 };
 // Two kernels: the default with 32 query rows per wave and `waves` = 8 or 12 waves per work item, and a
 // wide one with 4 waves x 64 rows (software-pipelined); one workgroup per CU in all cases.

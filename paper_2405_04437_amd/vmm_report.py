@@ -368,8 +368,84 @@ def prefill_admission(P, torch, W, quick):
     print()
 
 
+def fused_append(P, torch, W, quick):
+    import time
+
+    print("## 8. KV append as a launch of its own vs fused into the attention kernel\n")
+    print("Wall time per call on the launch stream (calls queued back to back, one synchronisation at the end).\n")
+    print("| path | separate append_kv + attention us | fused us | saved |")
+    print("|---|---|---|---|")
+    from paper_2405_04437_amd.runtime import KvSession
+
+    def wall(fn, iters, warm):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / iters
+
+    # decode: Yi-6B shape, 32 requests x 8192 tokens, the newest token of each appended in the same call
+    n, ctx = 32, 8192
+    s, ids, shape, gen = _decode_session(P, torch, W, 2 * MiB, 0, n=n, ctx=ctx, layers=1)
+    q = torch.randn((n, shape.num_q_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    kn = torch.randn((n, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    o = torch.empty_like(q)
+    lens = [ctx] * n
+    before = [ctx - 1] * n
+    cu = list(range(n + 1))
+    ws = s.workspace(lens)
+    scale = W.softmax_scale(shape.head_dim)
+    stream = s.stream
+
+    def dec_sep():
+        s.va.append_kv(0, stream, kn, kn, ids, cu, before)
+        s.va.attn_decode(0, stream, q, o, ids, lens, scale, ws, ws.numel())
+
+    a = wall(dec_sep, 300, 300)
+    b = wall(lambda: s.va.attn_decode_append(0, stream, q, kn, kn, o, ids, lens, scale, ws, ws.numel()), 300, 300)
+    print(f"| decode, 32 requests x 8192 tokens (Yi-6B shape) | {a:.1f} | {b:.1f} | {a - b:.1f} us ({100 * (a - b) / a:.1f} %) |")
+    s.close()
+
+    # prefill: the Llama-3-8B prefill batch of the benchmark (8 prompts, 105784 tokens)
+    wl = W.config(2)
+    shape = wl.shape
+    kv_lens = [int(x) for x in wl.kv_lens]
+    G = 2 * MiB
+    per = (max(kv_lens) * shape.token_bytes + G - 1) // G * G
+    s = KvSession(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, len(kv_lens), max(kv_lens), per * 2 * len(kv_lens), 1, G)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(4)
+    ids = [s.admit(L) for L in kv_lens]
+    s.step()
+    cu = [0]
+    for L in kv_lens:
+        cu.append(cu[-1] + L)
+    tot = cu[-1]
+    q = torch.empty((tot, shape.num_q_heads, shape.head_dim), device="cuda", dtype=torch.bfloat16)
+    for a0 in range(0, tot, 16384):
+        b0 = min(tot, a0 + 16384)
+        q[a0:b0] = torch.randn((b0 - a0, shape.num_q_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    kn = torch.randn((tot, shape.num_kv_heads, shape.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    o = torch.empty_like(q)
+    zeros = [0] * len(kv_lens)
+    stream = s.stream
+
+    def pre_sep():
+        s.va.append_kv(0, stream, kn, kn, ids, cu, zeros)
+        s.va.attn_prefill(0, stream, q, o, ids, cu, kv_lens, scale)
+
+    a = wall(pre_sep, 3 if quick else 6, 2)
+    b = wall(lambda: s.va.attn_prefill_append(0, stream, q, kn, kn, o, ids, cu, kv_lens, scale), 3 if quick else 6, 2)
+    print(f"| prefill, 8 prompts / {tot} tokens (Llama-3-8B shape) | {a:.0f} | {b:.0f} | {a - b:.0f} us ({100 * (a - b) / a:.1f} %) |")
+    s.close()
+    print()
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
+    ap.add_argument("--only", type=int, default=0, help="run only the section with this number")
     ap.add_argument("--quick", action="store_true")
     args = ap.parse_args()
     import torch
@@ -382,14 +458,14 @@ def main() -> int:
 
     torch.cuda.set_stream(torch.cuda.Stream())
     print(f"# Memory-manager measurements on {torch.cuda.get_device_name(0)}\n")
-    print("Command: `python paper_2405_04437_amd/vmm_report.py" + (" --quick" if args.quick else "") + "`\n")
-    api_latency(P, args.quick)
-    page_size_effect(P, torch, W, args.quick)
-    latency_hiding(P, torch, W, args.quick)
-    prefill_admission(P, torch, W, args.quick)
-    paged_overhead(P, torch, W, args.quick)
-    slicing_effect(P, torch, W, args.quick)
-    fragmentation(P, W, args.quick)
+    print("Command: `python paper_2405_04437_amd/vmm_report.py" + (" --quick" if args.quick else "") + (f" --only {args.only}" if args.only else "") + "`\n")
+    sections = {1: lambda: api_latency(P, args.quick), 2: lambda: page_size_effect(P, torch, W, args.quick),
+                3: lambda: latency_hiding(P, torch, W, args.quick), 4: lambda: prefill_admission(P, torch, W, args.quick),
+                5: lambda: paged_overhead(P, torch, W, args.quick), 6: lambda: slicing_effect(P, torch, W, args.quick),
+                7: lambda: fragmentation(P, W, args.quick), 8: lambda: fused_append(P, torch, W, args.quick)}
+    for num, fn in sections.items():
+        if args.only in (0, num):
+            fn()
     return 0
 
 

@@ -226,3 +226,61 @@ def test_decode_with_fused_append_matches_oracle_and_fills_the_cache(Hq, H, D):
     check(tensor_to_f32(s.decode(0, q, ids, kv_lens, scale)), want, "plain decode after the fused append")
     assert s.va.attn_decode_append(0, s.stream, q[:2], k_new[:2], v_new[:2], o[:2], [ids[0], ids[0]], kv_lens[:2], scale, ws, ws.numel()) == -1
     s.close()
+
+
+@pytest.mark.parametrize("Hq,H,D", [(8, 2, 64), (32, 8, 128), (14, 2, 128)])
+def test_prefill_with_fused_append_matches_oracle_and_fills_the_cache(Hq, H, D):
+    """vattn_attn_prefill_append = append_kv + attn_prefill in one launch: the K/V rows of the query tokens are
+    taken from the caller's buffers, attended to, and stored at positions kv_len-q_len .. kv_len-1.  Chunks that
+    start on a tile boundary, inside a tile, at position 0, a single-token chunk and an empty one."""
+    import torch
+    import paper_2405_04437_amd as P
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
+
+    shape = W.Shape("t", Hq, H, D, 1)
+    q_lens = [300, 200, 1, 77, 0, 513, 129, 64]
+    offs = [1000, 0, 554, 323, 10, 64, 63, 1]
+    kv_lens = [q + o for q, o in zip(q_lens, offs)]
+    n = len(q_lens)
+    inp = W.draw_attention_inputs(shape, q_lens, kv_lens, seed=Hq + D + 1)
+    scale = W.softmax_scale(D)
+    s = _session(shape, n, max(kv_lens))
+    ids = [s.admit(L) for L in kv_lens]
+    s.step()
+    # the cache holds the first `off` tokens of each request; the positions of the chunk hold a poison pattern
+    cu_old = np.zeros(n + 1, dtype=np.int64); cu_old[1:] = np.cumsum(offs)
+    s.append(0, bits_to_tensor(np.concatenate([k[:o] for k, o in zip(inp.k, offs)])),
+             bits_to_tensor(np.concatenate([v[:o] for v, o in zip(inp.v, offs)])), ids, cu_old, [0] * n)
+    poison = torch.full((int(inp.cu_q[-1]), H, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    s.append(0, poison, poison, ids, inp.cu_q, offs)
+    k_new = bits_to_tensor(np.concatenate([k[o:] for k, o in zip(inp.k, offs)]))
+    v_new = bits_to_tensor(np.concatenate([v[o:] for v, o in zip(inp.v, offs)]))
+    q = bits_to_tensor(inp.q)
+    o = torch.empty_like(q)
+    rc = s.va.attn_prefill_append(0, s.stream, q, k_new, v_new, o, ids, inp.cu_q, kv_lens, scale)
+    assert rc == 0, P.last_error()
+    want = OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale)
+    check(tensor_to_f32(o), want, "fused append + prefill")
+    # the cache now holds the new rows: a plain prefill over it does the same arithmetic on the same bytes
+    o2 = s.prefill(0, q, ids, inp.cu_q, kv_lens, scale)
+    assert torch.equal(o.view(torch.int16), o2.view(torch.int16))
+    # a reqId with a non-empty chunk may appear only once
+    assert s.va.attn_prefill_append(0, s.stream, q[:500], k_new[:500], v_new[:500], o[:500], [ids[0], ids[0]], [0, 300, 500],
+                                    [kv_lens[0], kv_lens[0]], scale) == -1
+    s.close()
+
+
+def test_prefill_with_fused_append_is_refused_for_the_sliced_layout():
+    import torch
+    import paper_2405_04437_amd as P
+    from paper_2405_04437_amd.runtime import KvSession
+
+    shape = W.Shape("t", 8, 2, 64, 2)
+    s = KvSession(8, 2, 64, 2, 256, 8 * MiB, 2, 64 * KiB, flags=P.FLAG_TENSOR_SLICING)
+    r = s.admit(100)
+    s.step()
+    q = torch.zeros((100, 8, 64), dtype=torch.bfloat16, device="cuda")
+    kv = torch.zeros((100, 2, 64), dtype=torch.bfloat16, device="cuda")
+    assert s.va.attn_prefill_append(0, s.stream, q, kv, kv, torch.empty_like(q), [r], [0, 100], [100], 0.125) == -1
+    assert "slicing" in P.last_error()
+    s.close()

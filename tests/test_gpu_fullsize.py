@@ -210,4 +210,16 @@ def test_many_work_items_take_the_twelve_wave_kernel(Hq, H, D):
         want = OA.attention_request(qb, kv[r][0], kv[r][1], scale, rows=rows)
         got = tensor_to_f32(o[int(cu[r]):int(cu[r + 1])][torch.from_numpy(rows.astype(np.int64)).cuda()])
         check(got, want, f"12-wave prefill D={D} prompt {r}")
+    # The fused-append variant of the same launch: the chunks' K/V rows come from the caller, their cache
+    # positions hold a poison pattern beforehand; same arithmetic on the same bytes, so the same bits.
+    from paper_2405_04437_amd.runtime import bits_to_tensor
+    k_new = bits_to_tensor(np.concatenate([kv[r][0][offs[r]:] for r in range(len(q_lens))]))
+    v_new = bits_to_tensor(np.concatenate([kv[r][1][offs[r]:] for r in range(len(q_lens))]))
+    poison = torch.full_like(k_new, float("nan"))
+    sess.append(0, poison, poison, ids, cu, offs)
+    o2 = torch.empty_like(o)
+    assert sess.va.attn_prefill_append(0, sess.stream, q, k_new, v_new, o2, ids, cu, kv_lens, scale) == 0
+    assert torch.equal(o.view(torch.int16), o2.view(torch.int16))
+    o3 = sess.prefill(0, q, ids, cu, kv_lens, scale)       # and the cache was filled
+    assert torch.equal(o.view(torch.int16), o3.view(torch.int16))
     sess.close()
