@@ -246,12 +246,16 @@ int vattn_set_timing(vattn_ctx* ctx, int enabled);
 int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* launches);
 
 /* Tuning knobs of the split-K decode.  By default the library cuts the batch's 32-token tiles into as
- * many equal segments as one launch keeps resident on the chip.  set_decode_chunk fixes the segment
- * length instead (tokens, a multiple of 32; 0 = default).  set_decode_tuning chooses how many segments
- * are cut per resident workgroup slot (>= 1; 1 measured best).  Results are identical up to
+ * many segments as one launch keeps resident on the chip (one workgroup of four waves per CU), with
+ * lengths proportional to a weight per XCD (segment s runs on XCD s % 8).  set_decode_chunk fixes one
+ * segment length instead (tokens, a multiple of 32; 0 = default).  set_decode_tuning chooses how many
+ * segments are cut per resident workgroup slot (>= 1; 1 measured best).  set_decode_xcd_weights replaces
+ * the eight weights (host array, each in [0.25, 4]; NULL restores the default 1, 0.9, 1, 0.9, ... -
+ * measured on MI355X: the odd XCDs draw about 10 % less bandwidth).  Results are identical up to
  * floating-point summation order. */
 int vattn_set_decode_chunk(vattn_ctx* ctx, int tokens);
 int vattn_set_decode_tuning(vattn_ctx* ctx, int segments_per_slot);
+int vattn_set_decode_xcd_weights(vattn_ctx* ctx, const float* weights /*host, 8 values, or NULL*/);
 
 /* Selects the prefill kernel.  Both take 256 query rows per workgroup, one workgroup per CU:
  * 0 (default) = eight waves of 32 rows; 1 = four waves of 64 rows, every K/V fragment read from

@@ -71,6 +71,7 @@ def _load() -> ctypes.CDLL:
     lib.vattn_kernel_time.argtypes = [vp, ctypes.c_int, dp, i64p]
     lib.vattn_set_decode_chunk.argtypes = [vp, ctypes.c_int]
     lib.vattn_set_decode_tuning.argtypes = [vp, ctypes.c_int]
+    lib.vattn_set_decode_xcd_weights.argtypes = [vp, ctypes.c_void_p]
     lib.vattn_set_prefill_wide.argtypes = [vp, ctypes.c_int]
     lib.vattn_step_counters.argtypes = [vp, i64p, i64p, dp, dp, dp]
     lib.vattn_sync.argtypes = [vp]
@@ -79,7 +80,7 @@ def _load() -> ctypes.CDLL:
                  "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill", "vattn_attn_decode",
                  "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide",
                  "vattn_step_counters", "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
-                 "vattn_attn_prefill_append"):
+                 "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -91,7 +92,7 @@ EXPORTED = ["vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqi
             "vattn_decode_workspace_bytes", "vattn_attn_decode", "vattn_set_timing", "vattn_kernel_time",
             "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide", "vattn_step_counters",
             "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
-            "vattn_attn_prefill_append", "vattn_last_error"]
+            "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights", "vattn_last_error"]
 
 
 def last_error() -> str:
@@ -261,6 +262,14 @@ class Vattn:
 
     def set_decode_tuning(self, segments_per_slot: int) -> int:
         return lib.vattn_set_decode_tuning(self._h, segments_per_slot)
+
+    def set_decode_xcd_weights(self, weights=None) -> int:
+        if weights is None:
+            return lib.vattn_set_decode_xcd_weights(self._h, None)
+        w = np.ascontiguousarray(weights, dtype=np.float32)
+        if w.shape != (8,):
+            raise ValueError("eight weights, one per XCD")
+        return lib.vattn_set_decode_xcd_weights(self._h, w.ctypes.data)
 
 
 def vmm_microbench(page_group_bytes: int, count: int, device: int = 0):

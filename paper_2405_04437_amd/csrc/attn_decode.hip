@@ -3,8 +3,9 @@
 // What is computed is Eq. 2 of the paper for one query token per request, o = softmax(q K^T * scale) V,
 // with K, V read straight from the request's sub-tensor at base + reqId*S (Sec. 5.2.3) - the kernel
 // never consults a block table.  The contexts of all requests, cut into 32-token tiles, form one
-// global tile sequence that is split into equal segments, one per resident workgroup, so that every
-// workgroup moves the same number of bytes and the launch is a single balanced round.  Every
+// global tile sequence that is split into segments, one per resident workgroup, so that the launch is a
+// single round; the segment lengths follow the bandwidth each XCD draws (workgroup s runs on XCD s % 8,
+// and on this chip the odd XCDs finish an equal share about 10 % later than the even ones).  Every
 // (segment, KV head) pair is handled by ONE wavefront that keeps a running maximum m, a running sum l
 // and an un-normalised output for the query heads of its KV head (the split-K scheme the paper cites
 // as FlashDecoding); a segment that crosses a request boundary emits one partial per request.  A
@@ -39,7 +40,8 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 constexpr int kTile = 32;          // tokens per inner iteration of a wave
-constexpr int kMaxWaves = 8;       // waves (KV heads) per workgroup
+constexpr int kMaxWaves = 4;       // waves (KV heads) per workgroup, and waves per CU: more concurrent streams than
+                                   // this lower the bandwidth the memory system delivers (measured: 8 per CU -4 %)
 constexpr float kLog2e = 1.4426950408889634f;
 // Fourth dword of a gfx9-family raw buffer resource: 32-bit data format, no swizzle, no stride.
 constexpr int kRsrcWord3 = 0x00020000;
@@ -88,8 +90,8 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
 
     // this segment's slice of the global tile sequence, and the request its first tile belongs to
     const int seg = blockIdx.x;
-    const int T0 = seg * a.tiles_per_seg;
-    const int T1 = min(T0 + a.tiles_per_seg, a.total_tiles);
+    const int T0 = min((seg >> 3) * a.period + a.pre[seg & 7], a.total_tiles);
+    const int T1 = min((seg >> 3) * a.period + a.pre[(seg & 7) + 1], a.total_tiles);
     int lo = 0, hi = a.n;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -233,8 +235,8 @@ __global__ __launch_bounds__(kMaxWaves * 64) void decode_splitk_kernel(DecodeArg
 
     const int ntiles = g1 - g0;
     // One tile of K and V (16 loads of 16 B per lane) is in flight while the previous one is multiplied.
-    // (A second register set, two tiles in flight, was measured and bought nothing: with 8 waves per CU
-    // the memory system is already saturated.)
+    // (A second register set, two tiles in flight per wave, was measured with 8, 4 and 2 waves per CU and
+    // never gained: what the memory system rewards is few concurrent streams, not more bytes in flight.)
     issue_loads(kreg, vreg, 0);
     // Fused KV append (optional): the request's newest token, position kv_len - 1, has not been written to the
     // cache yet.  The one wave whose piece holds that token for this KV head puts the row into its LDS tile
@@ -289,12 +291,19 @@ __global__ __launch_bounds__(kReduceWaves * 64) void decode_reduce_kernel(Decode
     constexpr int V = D / 64;  // channels per lane
     const int req = blockIdx.x / a.Hq;
     const int head = blockIdx.x - req * a.Hq;
-    // partial slots of this request: segments floor(first tile / tps) .. floor(last tile / tps), + req
+    // partial slots of this request: the segments of its first .. last tile, + req
     int t_first, t_end;
     if constexpr (INL) { t_first = im.v[2 * a.n + req]; t_end = im.v[2 * a.n + req + 1]; }
     else { t_first = a.cu_tiles[req]; t_end = a.cu_tiles[req + 1]; }
-    const int c0 = t_first / a.tiles_per_seg + req;
-    const int c1 = (t_end - 1) / a.tiles_per_seg + req + 1;
+    auto seg_of = [&](int t) {   // the segment that holds tile t
+        const int p = t / a.period, r = t - p * a.period;
+        int x = 0;
+#pragma unroll
+        for (int i = 1; i < 8; ++i) x += r >= a.pre[i];
+        return p * 8 + x;
+    };
+    const int c0 = seg_of(t_first) + req;
+    const int c1 = seg_of(t_end - 1) + req + 1;
     const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
     __shared__ float sh_max[kReduceWaves];
     __shared__ float sh_acc[kReduceWaves][D];
@@ -351,7 +360,7 @@ static int waves_per_workgroup(int Hq, int H) {
     return units < kMaxWaves ? units : kMaxWaves;
 }
 
-// A CU holds kMaxWaves waves of this kernel (LDS bound: one wave-private K/V stage each).
+// A CU is given kMaxWaves waves of this kernel.
 int decode_resident_workgroups(int Hq, int H, int D, int num_cus) {
     (void)D;
     const int units = H * ((Hq / H + 15) / 16);
@@ -368,7 +377,12 @@ bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t
     const int hb_per_kv = (group + 15) / 16;
     const int units = a.H * hb_per_kv;
     const int waves = waves_per_workgroup(a.Hq, a.H);
-    dim3 grid(static_cast<unsigned>(a.num_segs), static_cast<unsigned>((units + waves - 1) / waves));
+    // Workgroups are dealt to the XCDs in launch order, x fastest: with several workgroups per segment (grid.y)
+    // the x extent is padded to a multiple of 8 so that segment s still lands on XCD s % 8 in every row; the
+    // padding segments are empty.
+    const unsigned ygrid = static_cast<unsigned>((units + waves - 1) / waves);
+    const unsigned xgrid = ygrid > 1 ? (static_cast<unsigned>(a.num_segs) + 7u) / 8u * 8u : static_cast<unsigned>(a.num_segs);
+    dim3 grid(xgrid, ygrid);
     dim3 block(static_cast<unsigned>(waves * 64));
     static bool allowed[8] = {};  // per kernel variant
     auto launch = [&](auto kernel, size_t wave_lds, int variant) -> bool {

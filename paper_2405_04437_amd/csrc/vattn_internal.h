@@ -81,11 +81,14 @@ struct DecodeArgs {
     int Hq, H, D;
     int row_stride;                         // bytes between consecutive tokens of the layer
     // Split-K partition: the contexts of all requests, cut into 32-token tiles, form one global tile
-    // sequence (request-major).  Segment s owns tiles [s*tiles_per_seg, (s+1)*tiles_per_seg); a segment
+    // sequence (request-major), cut into periods of `period` tiles; segment s owns tiles
+    // [(s/8)*period + pre[s%8], (s/8)*period + pre[s%8 + 1]) - eight segment lengths that repeat, one per XCD
+    // (segment s runs on XCD s % 8), so that XCDs which draw less bandwidth get shorter segments.  A segment
     // that crosses a request boundary produces one partial per request it touches.  The partial of
     // (segment s, request r) lives in slot s + r (strictly increasing along the sequence, so unique).
     const int32_t* reqids; const int32_t* kv_lens; const int32_t* cu_tiles;  // device: n, n, n+1
-    int n; int total_tiles; int tiles_per_seg; int num_segs;
+    int n; int total_tiles; int num_segs;
+    int period; int pre[9];                 // pre[0] = 0 <= pre[1] <= ... <= pre[8] = period
     float scale;
     float* part_o;   // [num_segs + n, Hq, D] un-normalised partial outputs
     float* part_ml;  // [num_segs + n, Hq, 2] running max (log2 domain) and partial sum
@@ -136,6 +139,7 @@ struct vattn_ctx {
     bool timing = false;
     int decode_chunk = 0;
     int decode_oversub = 1;  // segments per resident workgroup slot
+    float decode_xcd_weight[8] = {1.f, 0.9f, 1.f, 0.9f, 1.f, 0.9f, 1.f, 0.9f};   // relative segment length per XCD
     bool prefill_wide = false;
     int num_cus = 0;
 };

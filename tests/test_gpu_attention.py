@@ -56,6 +56,29 @@ def test_decode_invariant_to_chunk_size(chunk):
     check(got, want, f"decode chunk={chunk}")
 
 
+@pytest.mark.parametrize("weights", [None, [1] * 8, [4, 0.25, 1, 1, 0.25, 4, 2, 0.5], [0.25, 0.25, 0.25, 0.25, 0.25, 0.25, 0.25, 4]])
+def test_decode_invariant_to_xcd_weights(weights):
+    """Segment lengths that differ per XCD (the default, equal ones and two lopsided sets) change only where the
+    contexts are cut; long enough contexts that the weighted split is in effect, ragged ends included."""
+    import paper_2405_04437_amd as P
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
+
+    shape = W.YI_6B
+    kv_lens = [9000, 12001, 7000, 15000, 11007, 13001, 33, 1]
+    n = len(kv_lens)
+    inp = W.draw_attention_inputs(shape, [1] * n, kv_lens, seed=77)
+    scale = W.softmax_scale(shape.head_dim)
+    s = _session(shape, n, max(kv_lens))
+    reqids = s.load_contexts(inp.k, inp.v)
+    if weights is not None:
+        assert s.va.set_decode_xcd_weights(weights) == 0, P.last_error()
+    got = tensor_to_f32(s.decode(0, bits_to_tensor(inp.q), reqids, kv_lens, scale))
+    assert s.va.set_decode_xcd_weights([1, 1, 1, 1, 1, 1, 1, 0.1]) == -1 and "weights" in P.last_error()
+    assert s.va.set_decode_xcd_weights(None) == 0
+    s.close()
+    check(got, OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale), f"decode with XCD weights {weights}")
+
+
 @pytest.mark.parametrize("G", [4 * KiB, 64 * KiB, 2 * MiB])
 def test_decode_invariant_to_page_group_size(G):
     shape = W.LLAMA3_8B
