@@ -401,9 +401,11 @@ int prefill_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void*
     const size_t off_items = align_up(off_kv + sizeof(int32_t) * n, 16);
     const size_t off_tab = align_up(off_items + sizeof(PrefillItem) * per_xcd * 8, 16);
     const size_t tab_bytes = paged ? sizeof(int32_t) * static_cast<size_t>(n) * paged->table_stride : 0;
-    const size_t bytes = off_tab + tab_bytes;
+    const size_t off_ctr = align_up(off_tab + tab_bytes, 16);   // queue counters, uploaded as zeros with the rest
+    const size_t bytes = off_ctr + 8 * sizeof(int32_t);
     char *h, *d;
     if (!ctx->ring.acquire(bytes, &h, &d)) return -1;
+    std::memset(h + off_ctr, 0, 8 * sizeof(int32_t));
     if (reqids) std::memcpy(h, reqids, sizeof(int32_t) * n);
     else std::memset(h, 0, sizeof(int32_t) * n);
     if (paged) std::memcpy(h + off_tab, paged->table, tab_bytes);
@@ -433,6 +435,7 @@ int prefill_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void*
     a.kv_lens = reinterpret_cast<const int32_t*>(d + off_kv);
     a.items = reinterpret_cast<const PrefillItem*>(d + off_items);
     a.items_per_xcd = static_cast<int>(per_xcd); a.n = n; a.scale = scale; a.waves = waves;
+    a.queue_heads = reinterpret_cast<int*>(d + off_ctr); a.num_cus = ctx->num_cus;
     if (fresh) { a.k_new = fresh->k_new; a.v_new = fresh->v_new; }
     LaunchEvents ev;
     if (ctx->timing && !ctx->timers[1].next(&ev.start, &ev.stop)) return -1;

@@ -18,6 +18,10 @@
 //    the host builds one work queue per XCD and gives each XCD whole (request, KV head) streams; the
 //    query heads of a group and neighbouring query tiles then run on the same XCD at the same time
 //    and share the K/V stream through that XCD's L2.
+//  * Workgroups are persistent: one per CU, each takes the next slot of its XCD's queue from an atomic
+//    counter and, once that queue is drained, helps with the queues of the other XCDs (the XCDs do not
+//    run at the same speed).  Starting a new workgroup per work item instead left each CU idle for about
+//    10 us per item.
 //  * Optional fused KV append (template flag FUSED): the chunk's own K/V rows are read from the caller's
 //    arrays and stored into the cache by the same launch (what Sec. 7.1 of the paper does with a copy).
 #include <hip/hip_runtime.h>
@@ -89,11 +93,27 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
     const int l = tid & 63;
     const int group = a.Hq / a.H;
 
-    // work item: queue of this XCD, slot bid/8; the heads of a group are adjacent slots
-    const int xcd = blockIdx.x & 7;
-    const int slot = blockIdx.x >> 3;
+    // persistent workgroup: takes the next slot of its XCD's queue; when that is drained, of the others
+    __shared__ int sh_item[2];
+    const int cap = a.items_per_xcd * group;
+    int xcd = blockIdx.x & 7;
+  for (;;) {
+    if (tid == 0) {
+        int got = -1, from = xcd;
+        for (int tries = 0; tries < 8 && got < 0; ++tries) {
+            const int x = (xcd + tries) & 7;
+            if (__hip_atomic_load(&a.queue_heads[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < cap) {
+                const int s2 = atomicAdd(&a.queue_heads[x], 1);
+                if (s2 < cap && a.items[static_cast<int64_t>(x) * a.items_per_xcd + s2 / group].req >= 0) { got = s2; from = x; }
+            }
+        }
+        sh_item[0] = got; sh_item[1] = from;
+    }
+    __syncthreads();
+    const int slot = __builtin_amdgcn_readfirstlane(sh_item[0]);
+    xcd = __builtin_amdgcn_readfirstlane(sh_item[1]);
+    if (slot < 0) return;
     const PrefillItem it = a.items[static_cast<int64_t>(xcd) * a.items_per_xcd + slot / group];
-    if (it.req < 0) return;  // padding entry (uniform for the whole workgroup)
     const int head = it.kvh * group + slot % group;
     const int req = it.req;
     const int q_begin = a.cu_q[req];
@@ -402,22 +422,32 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
                 *reinterpret_cast<u32x2*>(orow + d * 2) = __builtin_bit_cast(u32x2, v);
             }
     }
+    __syncthreads();   // every wave is done with the LDS ring and with sh_item
+  }
 }
 
 }  // namespace
 
 bool launch_prefill(const PrefillArgs& a_in, hipStream_t stream, LaunchEvents ev) {
     const int group = a_in.Hq / a_in.H;
-    dim3 grid(static_cast<unsigned>(8 * a_in.items_per_xcd * group));
-    if (grid.x == 0) return true;
+    const unsigned all_slots = static_cast<unsigned>(8 * a_in.items_per_xcd * group);
+    if (all_slots == 0) return true;
     const PrefillArgs& a = a_in;
-    static bool allowed[8] = {};  // per kernel variant
+    // Persistent workgroups: as many as the chip keeps resident (asked of the runtime once per kernel
+    // variant), a multiple of 8 so that every XCD gets the same number; each drains the queues by itself.
+    static int resident_per_cu[8] = {};  // per kernel variant; 0 = not asked yet
     auto launch = [&](auto kernel, int lds, int variant) -> bool {
-        if (!allowed[variant]) {  // dynamic LDS above 64 KiB has to be allowed once per kernel
+        const int threads = a.waves * 64;
+        if (resident_per_cu[variant] == 0) {
+            // dynamic LDS above 64 KiB has to be allowed once per kernel
             if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds), "hipFuncSetAttribute")) return false;
-            allowed[variant] = true;
+            int per_cu = 0;
+            if (!hip_ok(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, static_cast<size_t>(lds)), "hipOccupancyMaxActiveBlocksPerMultiprocessor")) return false;
+            resident_per_cu[variant] = per_cu > 0 ? per_cu : 1;
         }
-        hipExtLaunchKernelGGL(kernel, grid, dim3(static_cast<unsigned>(a.waves * 64)), static_cast<size_t>(lds), stream, ev.start, ev.stop, 0, a);
+        const unsigned resident = static_cast<unsigned>(resident_per_cu[variant] * a.num_cus) / 8u * 8u;
+        const dim3 grid(all_slots < resident ? all_slots : (resident ? resident : 8u));
+        hipExtLaunchKernelGGL(kernel, grid, dim3(static_cast<unsigned>(threads)), static_cast<size_t>(lds), stream, ev.start, ev.stop, 0, a);
         return true;
     };
     bool ok;

@@ -112,6 +112,8 @@ struct PrefillArgs {
     const int32_t* reqids; const int32_t* cu_q; const int32_t* kv_lens;   // device
     const PrefillItem* items;               // device: 8 queues of items_per_xcd entries each
     int items_per_xcd; int n;
+    int* queue_heads;                       // device: 8 counters, zero at launch: next slot of each XCD's queue (default kernel)
+    int num_cus;
     int waves;                              // default kernel: waves per workgroup (8 or 12); a work item is 32*waves rows
     // Paged comparison variant only (default kernel): k_base / v_base are block pools [num_blocks, block_tokens,
     // H, D]; block_table[req * table_stride + j] names the block with tokens j*block_tokens .. of batch slot req.
