@@ -184,7 +184,7 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q /*
 int64_t vattn_decode_workspace_bytes(vattn_ctx* ctx, const int64_t* kv_lens /*host*/, int n);
 
 /* Decode attention, one query token per request: q, o [n, Hq, D] bf16 (device).  Runs a split-K
- * kernel over equal segments of the batch's KV tiles followed by a reduce kernel that merges the
+ * kernel over segments of the batch's KV tiles (one per resident workgroup) followed by a reduce kernel that merges the
  * partials of each request (running maximum and sum) and writes bf16.  workspace: device memory
  * of at least vattn_decode_workspace_bytes(), 256-byte aligned, private to this call until the
  * stream has passed it. */
@@ -257,10 +257,11 @@ int vattn_set_decode_chunk(vattn_ctx* ctx, int tokens);
 int vattn_set_decode_tuning(vattn_ctx* ctx, int segments_per_slot);
 int vattn_set_decode_xcd_weights(vattn_ctx* ctx, const float* weights /*host, 8 values, or NULL*/);
 
-/* Selects the prefill kernel.  Both take 256 query rows per workgroup, one workgroup per CU:
- * 0 (default) = eight waves of 32 rows; 1 = four waves of 64 rows, every K/V fragment read from
- * LDS feeds two matrix instructions, software-pipelined (measured slower).  Same results up to
- * floating-point summation order. */
+/* Selects the prefill kernel, one workgroup per CU in both cases:
+ * 0 (default) = waves of 32 query rows, twelve per workgroup (384 rows) when the launch has many work
+ * items, else eight (256 rows); 1 = four waves of 64 rows, every K/V fragment read from LDS feeds two
+ * matrix instructions, software-pipelined (measured slower).  Same results up to floating-point
+ * summation order. */
 int vattn_set_prefill_wide(vattn_ctx* ctx, int enabled);
 
 const char* vattn_last_error(void);
