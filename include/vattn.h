@@ -159,6 +159,14 @@ int vattn_sync(vattn_ctx* ctx);
  * Needs no context.  `bytes` must be a multiple of the allocation granularity. */
 int vattn_vmm_microbench(int device, int64_t bytes, int count, double* out_us /*host*/);
 
+/* Matrix-pipe micro-benchmark for the roofline of the prefill kernel (the bf16 contractions of Eq. 2): two
+ * waves per SIMD on every CU run `rounds` rounds of four independent v_mfma_f32_32x32x16_bf16 with operands
+ * held in registers.  normal_operands = 0: all-zero operands (the chip keeps its full clock); 1: N(0,1)
+ * operands, the value distribution of the workloads here (the chip lowers its clock to hold its power limit).
+ * out[0] = dense TFLOP/s over the launch, out[1] = shader clock in MHz seen inside the kernel.  Needs no
+ * context; allocates and frees a few KiB of device memory; synchronises the device. */
+int vattn_mfma_microbench(int device, int normal_operands, int rounds, double* out /*host, 2 values*/);
+
 /* ---- the attention path (Eq. 2 of the paper, evaluated per request) -------------------------- */
 
 /* KV append ("a single tensor copy", Sec. 7.1): copies the new rows k_new/v_new [sum q_len, H, D]

@@ -76,11 +76,13 @@ def _load() -> ctypes.CDLL:
     lib.vattn_step_counters.argtypes = [vp, i64p, i64p, dp, dp, dp]
     lib.vattn_sync.argtypes = [vp]
     lib.vattn_vmm_microbench.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, dp]
+    lib.vattn_mfma_microbench.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, dp]
     for name in ("vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_query",
                  "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill", "vattn_attn_decode",
                  "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide",
                  "vattn_step_counters", "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
-                 "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights"):
+                 "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights",
+                 "vattn_mfma_microbench"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -92,7 +94,8 @@ EXPORTED = ["vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqi
             "vattn_decode_workspace_bytes", "vattn_attn_decode", "vattn_set_timing", "vattn_kernel_time",
             "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide", "vattn_step_counters",
             "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
-            "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights", "vattn_last_error"]
+            "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights",
+            "vattn_mfma_microbench", "vattn_last_error"]
 
 
 def last_error() -> str:
@@ -278,3 +281,11 @@ def vmm_microbench(page_group_bytes: int, count: int, device: int = 0):
     if lib.vattn_vmm_microbench(device, page_group_bytes, count, out) != 0:
         raise VattnError("vattn_vmm_microbench: " + last_error())
     return list(out)
+
+
+def mfma_microbench(normal_operands: bool, rounds: int = 100000, device: int = 0):
+    """(dense bf16 TFLOP/s, shader clock MHz) of a register-only MFMA loop on every CU (see vattn.h)."""
+    out = (ctypes.c_double * 2)()
+    if lib.vattn_mfma_microbench(device, 1 if normal_operands else 0, rounds, out) != 0:
+        raise VattnError("vattn_mfma_microbench: " + last_error())
+    return out[0], out[1]

@@ -174,6 +174,11 @@ int vattn_vmm_microbench(int device, int64_t bytes, int count, double* out_us) {
     return vmm_microbench(device, bytes, count, out_us) ? 0 : -1;
 }
 
+int vattn_mfma_microbench(int device, int normal_operands, int rounds, double* out) {
+    if (!out) { set_error("mfma_microbench: null output"); return -1; }
+    return mfma_microbench(device, normal_operands != 0, rounds, &out[0], &out[1]) ? 0 : -1;
+}
+
 int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new, const void* v_new,
                     const int32_t* reqids, const int32_t* cu_q, const int64_t* kv_len_before, int n) {
     if (!check_ctx_layer(ctx, layer, "append_kv")) return -1;

@@ -19,6 +19,7 @@ bool hip_ok(hipError_t e, const char* what);  // records the error text and retu
 const VmmOps& hip_vmm_ops();
 const VmmOps& hip_static_ops();
 bool vmm_microbench(int device, int64_t bytes, int count, double* out_us);
+bool mfma_microbench(int device, bool normal_operands, int rounds, double* tflops, double* shader_mhz);
 
 // ---------------------------------------------------------------------------------------------
 // Pinned staging ring for the small index arrays every attention call uploads.

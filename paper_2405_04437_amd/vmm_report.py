@@ -443,6 +443,18 @@ def fused_append(P, torch, W, quick):
     print()
 
 
+def matrix_pipe(P):
+    print("## 9. What the matrix pipes sustain: register-only MFMA loop, two waves per SIMD on every CU\n")
+    print("`v_mfma_f32_32x32x16_bf16`, operands in registers, no LDS or memory traffic in the timed loop; shader clock read")
+    print("inside the kernel (cycle counter / 100 MHz counter).  N(0,1) is the value distribution of the attention workloads.\n")
+    print("| operands | dense bf16 TFLOP/s | shader clock MHz | fraction of the 2.5 PFLOP/s peak |")
+    print("|---|---|---|---|")
+    for name, normal in (("all zero", False), ("N(0,1)", True)):
+        best = max(P.mfma_microbench(normal, 200000) for _ in range(3))
+        print(f"| {name} | {best[0]:.0f} | {best[1]:.0f} | {best[0] / 2500:.2f} |")
+    print()
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--only", type=int, default=0, help="run only the section with this number")
@@ -462,7 +474,8 @@ def main() -> int:
     sections = {1: lambda: api_latency(P, args.quick), 2: lambda: page_size_effect(P, torch, W, args.quick),
                 3: lambda: latency_hiding(P, torch, W, args.quick), 4: lambda: prefill_admission(P, torch, W, args.quick),
                 5: lambda: paged_overhead(P, torch, W, args.quick), 6: lambda: slicing_effect(P, torch, W, args.quick),
-                7: lambda: fragmentation(P, W, args.quick), 8: lambda: fused_append(P, torch, W, args.quick)}
+                7: lambda: fragmentation(P, W, args.quick), 8: lambda: fused_append(P, torch, W, args.quick),
+                9: lambda: matrix_pipe(P)}
     for num, fn in sections.items():
         if args.only in (0, num):
             fn()

@@ -222,3 +222,16 @@ def test_pool_larger_than_the_mapping_limit_is_refused():
     # the statically backed baseline maps nothing and is not limited
     va = P.Vattn(1, 2, 4096, 8, 2, 64, (cap + 10) * G, G, flags=P.FLAG_STATIC_BACKING)
     va.destroy()
+
+
+def test_mfma_microbench_reports_rate_and_clock():
+    """The matrix-pipe micro-benchmark: zero operands run at least as fast as N(0,1) operands, both report a
+    plausible dense bf16 rate (below the 2.5 PFLOP/s peak, far above the vector unit) and shader clock."""
+    import paper_2405_04437_amd as P
+
+    tz, cz = P.mfma_microbench(False, 20000)
+    tn, cn = P.mfma_microbench(True, 20000)
+    assert 300 < tn <= tz * 1.02 and tz < 2600, (tz, tn)
+    assert 500 < cn <= cz * 1.02 and cz < 2600, (cz, cn)
+    with pytest.raises(P.VattnError):
+        P.mfma_microbench(True, 0)
