@@ -126,23 +126,26 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
     torch_stream = torch.cuda.current_stream()
 
     def one_step(i):
+        arrivals = []
         if churn:  # config 4: ~10% of the requests finish and as many arrive, reusing backed reqIds
             k = max(1, int(round(0.10 * n)))
-            arrivals = []
             for slot in rng.choice(n, size=k, replace=False):
                 seq[ids[slot]] = 0
                 assert va.free_reqid(int(ids[slot])) == 0
                 lens[slot] = int(rng.integers(wl.extra["ctx_range"][0], wl.extra["ctx_range"][1], endpoint=True))
                 ids[slot] = va.alloc_reqid()
-                seq[ids[slot]] = lens[slot]
                 arrivals.append(slot)
-            assert va.step(seq) == 0
+        seq[ids] = lens + 1                # newcomers: their context and its first generated token
+        assert va.step(seq) == 0
+        if churn:
+            # The memory management above ran while the GPU was still busy with the previous iteration (Sec. 6.1.1
+            # of the paper: allocation overlapped with compute; nothing is unmapped under the deferred policy, and
+            # mapping does not disturb running kernels).  That iteration's output is needed before this one is launched.
+            torch_stream.synchronize()
             for slot in arrivals:  # the newcomer's context is written in place (contiguous copy)
                 L = int(lens[slot])
                 for layer in range(layers):
                     assert va.append_kv(layer, stream, kbig[:L], vbig[:L], ids[slot:slot + 1], [0, L], [0]) == 0
-        seq[ids] = lens + 1
-        assert va.step(seq) == 0
         if whole_model:                   # every layer: the new K/V row rides in that layer's decode kernel
             for layer in range(layers):
                 assert va.attn_decode_append(layer, stream, q, knew, vnew, o, ids, lens + 1, scale, ws, ws.numel()) == 0
@@ -153,9 +156,10 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
                 if layer != att:
                     assert va.append_kv(layer, stream, knew, vnew, ids, cu, lens) == 0
         lens[:] += 1
-        # iteration boundary of the serving loop (Algorithm 1): the framework needs this iteration's
-        # output on the host before it can schedule the next one
-        torch_stream.synchronize()
+        if not churn:
+            # iteration boundary of the serving loop (Algorithm 1): the framework needs this iteration's
+            # output on the host before it can schedule the next one
+            torch_stream.synchronize()
 
     launches_per_step = layers if whole_model else 1
 
@@ -375,7 +379,7 @@ def main() -> int:
                                         "traffic_detail": _measured_traffic("prefill_C3")}
     if args.only == "all":
         wl4 = W.config(3)
-        d4 = run_decode(args, torch, W, wl4, max(10, args.steps // 10), 10, layers=1, with_oracle=False, churn=True)
+        d4 = run_decode(args, torch, W, wl4, max(20, args.steps // 5), 10, layers=1, with_oracle=False, churn=True)
         also["C4_yi34b_mixed_decode_part"] = {"gbs_step": d4["gbs_step"], "gbs_kernel": d4["gbs_kernel"],
                                               "frac_of_hbm_peak_kernel": d4["gbs_kernel"] / HBM_PEAK_GBS,
                                               "ms_per_step": d4["ms_per_step"], "kernel_ms": d4["kernel_ms"],
