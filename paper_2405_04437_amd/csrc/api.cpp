@@ -292,6 +292,17 @@ int decode_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* 
     a.n = n; a.total_tiles = static_cast<int>(total); a.num_segs = plan.num_segs; a.scale = scale;
     a.period = plan.period;
     for (int x = 0; x < 9; ++x) a.pre[x] = plan.pre[x];
+    {
+        auto seg_of = [&](int64_t t) {
+            const int64_t p = t / plan.period, r = t % plan.period;
+            int x = 0;
+            for (int i = 1; i < 8; ++i) x += r >= plan.pre[i];
+            return p * 8 + x;
+        };
+        int64_t most = 1;
+        for (int r = 0; r < n; ++r) most = std::max<int64_t>(most, seg_of(h_cu[r + 1] - 1) - seg_of(h_cu[r]) + 1);
+        a.max_slots = static_cast<int>(most);
+    }
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + part_o_bytes);
     const InlineMeta* imp = inl ? &im : nullptr;

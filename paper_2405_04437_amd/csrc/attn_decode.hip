@@ -351,6 +351,54 @@ __global__ __launch_bounds__(kReduceWaves * 64) void decode_reduce_kernel(Decode
     }
 }
 
+// The same merge for requests that own few partials (a batch of many requests, the usual decode case): one
+// wave per (request, query head), four per workgroup, no LDS and no barrier - the lanes first share the
+// maximum, then walk the partials with independent multiply-adds.  An eighth of the waves of the kernel above.
+constexpr int kReduceFewPairs = 4;
+
+template <int D, bool INL>
+__global__ __launch_bounds__(kReduceFewPairs * 64) void decode_reduce_few_kernel(DecodeArgs a, InlineMeta im) {
+    constexpr int V = D / 64;  // channels per lane
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l = threadIdx.x & 63;
+    const int pair = blockIdx.x * kReduceFewPairs + w;
+    if (pair >= a.n * a.Hq) return;
+    const int req = pair / a.Hq;
+    const int head = pair - req * a.Hq;
+    int t_first, t_end;
+    if constexpr (INL) { t_first = im.v[2 * a.n + req]; t_end = im.v[2 * a.n + req + 1]; }
+    else { t_first = a.cu_tiles[req]; t_end = a.cu_tiles[req + 1]; }
+    auto seg_of = [&](int t) {   // the segment that holds tile t
+        const int p = t / a.period, r = t - p * a.period;
+        int x = 0;
+#pragma unroll
+        for (int i = 1; i < 8; ++i) x += r >= a.pre[i];
+        return p * 8 + x;
+    };
+    const int c0 = seg_of(t_first) + req;
+    const int c1 = seg_of(t_end - 1) + req + 1;
+
+    float M = -INFINITY;
+    for (int c = c0 + l; c < c1; c += 64) M = fmaxf(M, a.part_ml[(static_cast<int64_t>(c) * a.Hq + head) * 2]);
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) M = fmaxf(M, __shfl_xor(M, sft));   // finite: c1 > c0 always
+
+    float den = 0.f, acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+#pragma unroll 4
+    for (int c = c0; c < c1; ++c) {
+        const int64_t idx = static_cast<int64_t>(c) * a.Hq + head;
+        const float f = __builtin_amdgcn_exp2f(a.part_ml[idx * 2] - M);
+        den += f * a.part_ml[idx * 2 + 1];
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[e] += f * a.part_o[idx * D + l * V + e];
+    }
+    __bf16* dst = static_cast<__bf16*>(a.o) + (static_cast<int64_t>(req) * a.Hq + head) * D + l * V;
+    const float inv = 1.f / den;
+#pragma unroll
+    for (int e = 0; e < V; ++e) dst[e] = static_cast<__bf16>(acc[e] * inv);
+}
+
 }  // namespace
 
 static const InlineMeta kNoInline{};
@@ -408,6 +456,18 @@ bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t
 
 bool launch_decode_reduce(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev) {
     const InlineMeta& meta = im ? *im : kNoInline;
+    if (a.max_slots <= 16) {   // few partials per request: one wave per (request, head)
+        const dim3 grid(static_cast<unsigned>((a.n * a.Hq + kReduceFewPairs - 1) / kReduceFewPairs));
+        const dim3 block(kReduceFewPairs * 64);
+        if (a.D == 128) {
+            if (a.inline_meta) hipExtLaunchKernelGGL((decode_reduce_few_kernel<128, true>), grid, block, 0, stream, ev.start, ev.stop, 0, a, meta);
+            else hipExtLaunchKernelGGL((decode_reduce_few_kernel<128, false>), grid, block, 0, stream, ev.start, ev.stop, 0, a, meta);
+        } else {
+            if (a.inline_meta) hipExtLaunchKernelGGL((decode_reduce_few_kernel<64, true>), grid, block, 0, stream, ev.start, ev.stop, 0, a, meta);
+            else hipExtLaunchKernelGGL((decode_reduce_few_kernel<64, false>), grid, block, 0, stream, ev.start, ev.stop, 0, a, meta);
+        }
+        return hip_ok(hipGetLastError(), "decode reduce launch");
+    }
     dim3 grid(static_cast<unsigned>(a.n * a.Hq));
     const dim3 block(kReduceWaves * 64);
     if (a.D == 128) {

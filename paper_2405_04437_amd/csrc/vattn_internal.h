@@ -90,6 +90,7 @@ struct DecodeArgs {
     const int32_t* reqids; const int32_t* kv_lens; const int32_t* cu_tiles;  // device: n, n, n+1
     int n; int total_tiles; int num_segs;
     int period; int pre[9];                 // pre[0] = 0 <= pre[1] <= ... <= pre[8] = period
+    int max_slots;                          // most partials any one request has (picks the reduce kernel)
     float scale;
     float* part_o;   // [num_segs + n, Hq, D] un-normalised partial outputs
     float* part_ml;  // [num_segs + n, Hq, 2] running max (log2 domain) and partial sum
