@@ -34,53 +34,9 @@ bool check_request(vattn_ctx* ctx, int reqid, int64_t kv_len, const char* fn) {
     return true;
 }
 
-// Split-K plan: the 32-token tiles of all requests form one sequence, cut into as many segments as one launch
-// keeps resident on the chip (or into segments of a fixed tile count when the caller set a chunk size).
-// Workgroup s of a launch runs on XCD s % 8, and the XCDs do not draw the same bandwidth (measured: the odd
-// ones finish an equal share about 10 % later), so segment lengths repeat with period 8 and follow the
-// per-XCD weights; the last period may be cut short by the end of the sequence.
-struct DecodePlan { int64_t total_tiles; int num_segs; int period; int pre[9]; };
 DecodePlan plan_decode(const vattn_ctx* ctx, const int64_t* kv_lens, int n) {
-    DecodePlan p{};
-    for (int i = 0; i < n; ++i) p.total_tiles += (kv_lens[i] + 31) / 32;
-    int64_t len[8];
-    if (ctx->decode_chunk > 0) {
-        for (int x = 0; x < 8; ++x) len[x] = ctx->decode_chunk / 32;
-    } else {
-        const int resident = decode_resident_workgroups(ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, ctx->cfg.head_dim, ctx->num_cus);
-        const int64_t segs = std::max<int64_t>(8, static_cast<int64_t>(resident) * ctx->decode_oversub / 8 * 8);
-        const int64_t periods = segs / 8;
-        const int64_t P = (p.total_tiles + periods - 1) / periods;     // tiles per period
-        if (P < 64) {   // short contexts: equal segments, as many as there are tiles if need be
-            const int64_t tps = std::max<int64_t>(1, (p.total_tiles + segs - 1) / segs);
-            for (int x = 0; x < 8; ++x) len[x] = tps;
-        } else {        // weighted lengths that add up to P (largest remainders get the leftover tiles)
-            double wsum = 0;
-            for (int x = 0; x < 8; ++x) wsum += ctx->decode_xcd_weight[x];
-            double frac[8];
-            int64_t used = 0;
-            for (int x = 0; x < 8; ++x) {
-                const double exact = P * ctx->decode_xcd_weight[x] / wsum;
-                len[x] = static_cast<int64_t>(exact);
-                frac[x] = exact - len[x];
-                used += len[x];
-            }
-            for (; used < P; ++used) {
-                int best = 0;
-                for (int x = 1; x < 8; ++x) if (frac[x] > frac[best]) best = x;
-                ++len[best]; frac[best] = -1;
-            }
-        }
-    }
-    int64_t acc = 0;
-    for (int x = 0; x < 8; ++x) { p.pre[x] = static_cast<int>(acc); acc += len[x]; }
-    p.pre[8] = static_cast<int>(acc);
-    p.period = p.pre[8];
-    const int64_t full = p.total_tiles / p.period, rest = p.total_tiles % p.period;
-    int tail = 0;
-    while (tail < 8 && p.pre[tail] < rest) ++tail;     // segments of the last, partial period that hold tiles
-    p.num_segs = static_cast<int>(std::max<int64_t>(1, full * 8 + tail));
-    return p;
+    const int resident = decode_resident_workgroups(ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, ctx->cfg.head_dim, ctx->num_cus);
+    return make_decode_plan(kv_lens, n, ctx->decode_chunk, resident, ctx->decode_oversub, ctx->decode_xcd_weight);
 }
 
 size_t decode_part_o_bytes(const vattn_ctx* ctx, const DecodePlan& p, int n) {
@@ -226,7 +182,7 @@ int64_t vattn_decode_workspace_bytes(vattn_ctx* ctx, const int64_t* kv_lens, int
         // In the balanced mode the segment count never exceeds the resident workgroup slots, whatever
         // the lengths: size for that bound so that the same workspace serves the batch as it grows.
         const int resident = decode_resident_workgroups(ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, ctx->cfg.head_dim, ctx->num_cus);
-        p.num_segs = std::max(8, resident * ctx->decode_oversub) + 8;
+        p.num_segs = decode_plan_max_segs(resident, ctx->decode_oversub);
     }
     return static_cast<int64_t>(decode_workspace_need(ctx, p, n));
 }
@@ -293,14 +249,9 @@ int decode_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* 
     a.period = plan.period;
     for (int x = 0; x < 9; ++x) a.pre[x] = plan.pre[x];
     {
-        auto seg_of = [&](int64_t t) {
-            const int64_t p = t / plan.period, r = t % plan.period;
-            int x = 0;
-            for (int i = 1; i < 8; ++i) x += r >= plan.pre[i];
-            return p * 8 + x;
-        };
         int64_t most = 1;
-        for (int r = 0; r < n; ++r) most = std::max<int64_t>(most, seg_of(h_cu[r + 1] - 1) - seg_of(h_cu[r]) + 1);
+        for (int r = 0; r < n; ++r)
+            most = std::max<int64_t>(most, decode_plan_segment_of(plan, h_cu[r + 1] - 1) - decode_plan_segment_of(plan, h_cu[r]) + 1);
         a.max_slots = static_cast<int>(most);
     }
     a.part_o = static_cast<float*>(workspace);

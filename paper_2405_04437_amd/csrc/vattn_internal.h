@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../../include/vattn.h"
+#include "decode_plan.h"
 #include "kv_memory.h"
 
 namespace vattn {
