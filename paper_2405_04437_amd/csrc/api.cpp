@@ -327,41 +327,11 @@ namespace {
 int prefill_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
                    const int32_t* cu_q, const int64_t* kv_lens, int n, float scale, const PagedKv* paged, const NewRows* fresh = nullptr) {
     const int H = ctx->cfg.num_kv_heads, Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
-    // 256 query rows per work item for both kernels; the wide one (four waves of 64 rows, software-pipelined)
-    // is opt-in: measured slower.
+    // the wide kernel (four waves of 64 rows, software-pipelined) is opt-in: measured slower
     const bool wide = ctx->prefill_wide && !paged && !fresh;
-    // Default kernel: twelve waves (384 rows per work item, three waves per SIMD) when that still leaves
-    // every CU several work items, else eight waves (256 rows).
-    int waves = 8;
-    if (!wide) {
-        int64_t items12 = 0;
-        for (int r = 0; r < n; ++r) items12 += (static_cast<int64_t>(cu_q[r + 1]) - cu_q[r] + 383) / 384 * Hq;
-        if (items12 >= 4 * static_cast<int64_t>(ctx->num_cus)) waves = 12;
-    }
-    const int BM = wide ? 256 : 32 * waves;
-    // One queue per XCD.  Workgroup ids are dealt to the 8 XCDs round-robin, so giving XCD x the
-    // streams (request, KV head, tile class) with index == x (mod 8) keeps all readers of one K/V
-    // stream behind the same L2.  KV heads are split into tile classes when there are fewer than 8.
-    const int nsplit = H < 8 ? (8 + H - 1) / H : 1;
-    struct Cost { PrefillItem it; int64_t cost; };
-    std::vector<Cost> queues[8];
-    for (int r = 0; r < n; ++r) {
-        const int ql = cu_q[r + 1] - cu_q[r];
-        const int tiles = (ql + BM - 1) / BM;
-        const int64_t off = kv_lens[r] - ql;
-        for (int t = 0; t < tiles; ++t) {
-            const int64_t visible = std::min<int64_t>(static_cast<int64_t>(t + 1) * BM, ql) + off;
-            for (int kvh = 0; kvh < H; ++kvh) {
-                const int x = (kvh * nsplit + t % nsplit + ((H * nsplit) % 8 ? r : 0)) & 7;
-                queues[x].push_back(Cost{PrefillItem{r, kvh, t, 0}, visible});
-            }
-        }
-    }
-    size_t per_xcd = 0;
-    for (auto& qx : queues) {
-        std::stable_sort(qx.begin(), qx.end(), [](const Cost& x, const Cost& y) { return x.cost > y.cost; });
-        per_xcd = std::max(per_xcd, qx.size());
-    }
+    const PrefillQueues queues = make_prefill_queues(cu_q, kv_lens, n, Hq, H, ctx->num_cus, wide);
+    const int waves = queues.waves;
+    const size_t per_xcd = static_cast<size_t>(queues.per_xcd);
     if (per_xcd == 0) return 0;
     const size_t off_cu = sizeof(int32_t) * n;
     const size_t off_kv = off_cu + sizeof(int32_t) * (n + 1);
@@ -379,10 +349,7 @@ int prefill_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void*
     std::memcpy(h + off_cu, cu_q, sizeof(int32_t) * (n + 1));
     int32_t* h_kv = reinterpret_cast<int32_t*>(h + off_kv);
     for (int r = 0; r < n; ++r) h_kv[r] = static_cast<int32_t>(kv_lens[r]);
-    PrefillItem* h_items = reinterpret_cast<PrefillItem*>(h + off_items);
-    for (int x = 0; x < 8; ++x)
-        for (size_t j = 0; j < per_xcd; ++j)
-            h_items[x * per_xcd + j] = j < queues[x].size() ? queues[x][j].it : PrefillItem{-1, 0, 0, 0};
+    std::memcpy(h + off_items, queues.items.data(), sizeof(PrefillItem) * per_xcd * 8);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!ctx->ring.commit(bytes, s)) return -1;
 

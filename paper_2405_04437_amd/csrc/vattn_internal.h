@@ -9,6 +9,7 @@
 
 #include "../../include/vattn.h"
 #include "decode_plan.h"
+#include "prefill_plan.h"
 #include "kv_memory.h"
 
 namespace vattn {
@@ -106,7 +107,6 @@ int decode_resident_workgroups(int Hq, int H, int D, int num_cus);  // workgroup
 bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});   // paged if a.block_table
 bool launch_decode_reduce(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});
 
-struct PrefillItem { int32_t req; int32_t kvh; int32_t q_tile; int32_t pad; };
 struct PrefillArgs {
     const void* q; void* o;                 // [sum q_len, Hq, D] bf16
     const char* k_base; const char* v_base; int64_t S;

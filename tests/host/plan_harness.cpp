@@ -1,6 +1,8 @@
-// Host build of the decode split-K planner (csrc/decode_plan.h).  Reads one request per line:
+// Host build of the launch planners (csrc/decode_plan.h, csrc/prefill_plan.h).  One request per line:
 //   chunk_tokens resident segments_per_slot w0 .. w7 len0 len1 ...
-// and prints: total_tiles num_segs max_segs period pre0 .. pre8
+//       -> total_tiles num_segs max_segs period pre0 .. pre8
+//   Q Hq H num_cus wide n q_len0 kv_len0 q_len1 kv_len1 ...
+//       -> waves rows_per_item per_xcd, then 8 * per_xcd triples req kvh q_tile (queue-major)
 #include <cstdio>
 #include <iostream>
 #include <sstream>
@@ -8,11 +10,26 @@
 #include <vector>
 
 #include "../../paper_2405_04437_amd/csrc/decode_plan.h"
+#include "../../paper_2405_04437_amd/csrc/prefill_plan.h"
 
 int main() {
     std::string line;
     while (std::getline(std::cin, line)) {
         std::istringstream in(line);
+        if (!line.empty() && line[0] == 'Q') {
+            char tag;
+            int Hq, H, cus, wide, n;
+            in >> tag >> Hq >> H >> cus >> wide >> n;
+            std::vector<int32_t> cu(1, 0);
+            std::vector<int64_t> kv;
+            for (int r = 0; r < n; ++r) { int q; long long k; in >> q >> k; cu.push_back(cu.back() + q); kv.push_back(k); }
+            const vattn::PrefillQueues pq = vattn::make_prefill_queues(cu.data(), kv.data(), n, Hq, H, cus, wide != 0);
+            std::printf("%d %d %d", pq.waves, pq.rows_per_item, pq.per_xcd);
+            for (const auto& it : pq.items) std::printf(" %d %d %d", it.req, it.kvh, it.q_tile);
+            std::printf("\n");
+            std::fflush(stdout);
+            continue;
+        }
         int chunk, resident, per_slot;
         float w[8];
         if (!(in >> chunk >> resident >> per_slot)) break;

@@ -1,7 +1,8 @@
-"""The decode split-K planner (csrc/decode_plan.h) built for the host: whatever the batch, the segments it
+"""The launch planners built for the host.  Decode split-K planner (csrc/decode_plan.h): whatever the batch, the segments it
 describes - recomputed here the way the kernels do, from `period` and the nine prefix values - cover every
 tile exactly once in order, stay inside the workspace bound, follow the per-XCD weights, and give every
-(segment, request) pair its own partial slot."""
+(segment, request) pair its own partial slot.  Prefill work queues (csrc/prefill_plan.h): every (request, KV head,
+query tile) sits in exactly one of the eight queues, longest first, padding only at the tails."""
 import os
 import subprocess
 
@@ -27,6 +28,15 @@ def planner():
         v = [int(x) for x in p.stdout.readline().split()]
         return {"total": v[0], "num_segs": v[1], "max_segs": v[2], "period": v[3], "pre": v[4:13]}
 
+    def queues(Hq, H, cus, wide, q_lens, kv_lens):
+        flat = [v for pair in zip(q_lens, kv_lens) for v in pair]
+        p.stdin.write(" ".join(str(x) for x in ["Q", Hq, H, cus, int(wide), len(q_lens), *flat]) + "\n")
+        p.stdin.flush()
+        v = [int(x) for x in p.stdout.readline().split()]
+        items = np.array(v[3:], dtype=np.int64).reshape(8, v[2], 3) if v[2] else np.zeros((8, 0, 3), dtype=np.int64)
+        return {"waves": v[0], "rows": v[1], "per_xcd": v[2], "items": items}
+
+    ask.queues = queues
     yield ask
     p.stdin.close()
     p.wait(timeout=30)
@@ -114,3 +124,44 @@ def test_short_batches_fall_back_to_equal_segments(planner):
     plan = planner(0, 256, 1, [4, 0.25, 1, 1, 0.25, 4, 2, 0.5], [100, 200, 50])       # 13 tiles
     check_plan(plan, [100, 200, 50])
     assert len(set(np.diff(plan["pre"]).tolist())) == 1 and plan["num_segs"] == 13
+
+
+@pytest.mark.parametrize("Hq,H", [(32, 8), (56, 8), (32, 4), (8, 2), (3, 3), (7, 1), (64, 16)])
+@pytest.mark.parametrize("wide", [False, True])
+def test_prefill_queues_hold_every_work_item_once(planner, Hq, H, wide):
+    rng = np.random.default_rng(Hq * 31 + H)
+    cases = [([0], [5]), ([1], [1]), ([300, 200, 1, 77, 0, 513], [1300, 200, 555, 400, 10, 577]),
+             (rng.integers(4096, 32768, endpoint=True, size=8).tolist(),) * 2, ([2048], [10240]), ([131072], [131072])]
+    for q_lens, kv_lens in cases:
+        pq = planner.queues(Hq, H, 256, wide, q_lens, kv_lens)
+        many = sum(-(-q // 384) for q in q_lens) * Hq >= 4 * 256
+        assert pq["waves"] == (12 if many and not wide else 8)
+        BM = pq["rows"]
+        assert BM == (256 if wide else 32 * pq["waves"])
+        want = {(r, kvh, t) for r, q in enumerate(q_lens) for t in range(-(-q // BM)) for kvh in range(H)}
+        seen = []
+        for x in range(8):
+            queue = pq["items"][x]
+            live = queue[queue[:, 0] >= 0]
+            assert np.all(queue[len(live):, 0] == -1)                     # padding only at the tail
+            seen += [tuple(int(v) for v in it) for it in live]
+            cost = [min((t + 1) * BM, q_lens[r]) + kv_lens[r] - q_lens[r] for r, _, t in live]
+            assert all(a >= b for a, b in zip(cost, cost[1:]))            # longest first
+        assert len(seen) == len(want) and set(seen) == want
+        assert pq["per_xcd"] * 8 >= len(want) and (pq["per_xcd"] == 0) == (len(want) == 0)
+
+
+def test_prefill_queues_keep_a_kv_stream_on_one_xcd(planner):
+    """All query tiles of one (request, KV head) - or of one tile class when there are fewer than 8 KV heads - share a queue."""
+    pq = planner.queues(32, 8, 256, False, [5000, 9000, 4097], [5000, 9000, 5097])
+    home = {}
+    for x in range(8):
+        for r, kvh, t in pq["items"][x]:
+            if r >= 0:
+                assert home.setdefault((int(r), int(kvh)), x) == x
+    pq = planner.queues(32, 4, 256, False, [5000, 9000, 4097], [5000, 9000, 5097])       # 4 KV heads: two tile classes each
+    home = {}
+    for x in range(8):
+        for r, kvh, t in pq["items"][x]:
+            if r >= 0:
+                assert home.setdefault((int(r), int(kvh), int(t) % 2), x) == x
