@@ -48,6 +48,20 @@ def test_decode_shapes_ragged_lengths(Hq, H, D):
     check(got, want, f"decode Hq={Hq} H={H} D={D}")
 
 
+@pytest.mark.parametrize("Hq,H,D", [(32, 4, 128), (8, 2, 64)])
+def test_decode_batch_larger_than_the_inline_index_arrays(Hq, H, D):
+    """More than 256 requests: reqIds, lengths and tile prefix sums no longer fit the kernel-argument segment and
+    travel through the staging ring instead (append, split-K, both reduce kernels: short contexts take the
+    one-wave reduce, the two long ones the general one)."""
+    shape = W.Shape("t", Hq, H, D, 1)
+    rng = np.random.default_rng(D)
+    kv_lens = rng.integers(1, 200, size=298).tolist() + [5000, 7001]
+    got, want, _ = _run_decode(shape, kv_lens, seed=3)
+    check(got, want, f"decode with {len(kv_lens)} requests")
+    got, want, _ = _run_decode(shape, kv_lens[:298], seed=4)
+    check(got, want, "decode with 298 short requests")
+
+
 @pytest.mark.parametrize("chunk", [32, 64, 256, 512, 4096])
 def test_decode_invariant_to_chunk_size(chunk):
     shape = W.YI_6B
