@@ -90,17 +90,18 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, ch
     ksteps = max(1, steps // 8) if whole_model else steps     # steps of the second, event-timed pass
     total_steps = steps + ksteps + warmup + 2
     ctx_hi = wl.extra["ctx_range"][1] if churn else 0
-    max_ctx = max(max(kv_lens), ctx_hi) + total_steps + 8
+    max_ctx = max(max(kv_lens), ctx_hi) + total_steps + 8 + 64
     G = 2 * MiB
     headroom = n // 4 + 4
     per_req = (max_ctx * shape.token_bytes + G - 1) // G * G
     budget = per_req * 2 * layers * (n + headroom)
-    if not churn:   # the page-groups these requests can reach by the last step, and a few spare rows
-        rows = sum((int(L + total_steps + 8) * shape.token_bytes + G - 1) // G for L in kv_lens) + 8
+    lookahead = 64 if background else 0
+    if not churn:   # the page-groups these requests can reach by the last step (look-ahead included), and a few spare rows
+        rows = sum((int(L + total_steps + 8 + lookahead) * shape.token_bytes + G - 1) // G for L in kv_lens) + 8
         budget = rows * G * 2 * layers
     sess = KvSession(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, n + headroom, max_ctx, budget, layers, G,
                      POLICY_DEFERRED, flags=FLAG_BACKGROUND if background else 0,
-                     lookahead_tokens=64 if background else 0)
+                     lookahead_tokens=lookahead)
     gen = torch.Generator(device="cuda"); gen.manual_seed(wl.seed)
     ids, host = _fill_contexts(sess, torch, gen, shape, kv_lens, layers, keep_host=with_oracle)
     for r, L in zip(ids, kv_lens):
