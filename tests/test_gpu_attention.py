@@ -93,6 +93,29 @@ def test_decode_invariant_to_xcd_weights(weights):
     check(got, OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale), f"decode with XCD weights {weights}")
 
 
+@pytest.mark.parametrize("per_slot", [2, 5, 64])
+def test_decode_invariant_to_segments_per_slot(per_slot):
+    """More, shorter segments than resident workgroups (set_decode_tuning): same result, and the workspace the
+    library asks for covers them."""
+    import paper_2405_04437_amd as P
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
+
+    shape = W.LLAMA3_8B
+    kv_lens = [9000, 12001, 33, 1, 20000]
+    n = len(kv_lens)
+    inp = W.draw_attention_inputs(shape, [1] * n, kv_lens, seed=per_slot)
+    scale = W.softmax_scale(shape.head_dim)
+    s = _session(shape, n, max(kv_lens))
+    reqids = s.load_contexts(inp.k, inp.v)
+    small = s.va.decode_workspace_bytes(kv_lens)
+    assert s.va.set_decode_tuning(per_slot) == 0, P.last_error()
+    assert s.va.decode_workspace_bytes(kv_lens) > small
+    got = tensor_to_f32(s.decode(0, bits_to_tensor(inp.q), reqids, kv_lens, scale))
+    assert s.va.set_decode_tuning(0) == -1 and s.va.set_decode_tuning(65) == -1
+    s.close()
+    check(got, OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale), f"decode with {per_slot} segments per slot")
+
+
 @pytest.mark.parametrize("G", [4 * KiB, 64 * KiB, 2 * MiB])
 def test_decode_invariant_to_page_group_size(G):
     shape = W.LLAMA3_8B
