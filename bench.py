@@ -313,7 +313,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards by request / KV head with no exchange "
-              "step; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "step); run with --gpus 1", file=sys.stderr)
         return 2
     import torch
 
