@@ -329,7 +329,7 @@ int prefill_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void*
     const int H = ctx->cfg.num_kv_heads, Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
     // the wide kernel (four waves of 64 rows, software-pipelined) is opt-in: measured slower
     const bool wide = ctx->prefill_wide && !paged && !fresh;
-    const PrefillQueues queues = make_prefill_queues(cu_q, kv_lens, n, Hq, H, ctx->num_cus, wide);
+    const PrefillQueues queues = make_prefill_queues(reqids, cu_q, kv_lens, n, Hq, H, ctx->num_cus, wide);
     const int waves = queues.waves;
     const size_t per_xcd = static_cast<size_t>(queues.per_xcd);
     if (per_xcd == 0) return 0;

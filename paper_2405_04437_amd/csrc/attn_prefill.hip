@@ -116,9 +116,9 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
     const PrefillItem it = a.items[static_cast<int64_t>(xcd) * a.items_per_xcd + slot / group];
     const int head = it.kvh * group + slot % group;
     const int req = it.req;
-    const int q_begin = a.cu_q[req];
-    const int q_len = a.cu_q[req + 1] - q_begin;
-    const int kv_len = a.kv_lens[req];
+    const int q_begin = it.q_begin;
+    const int q_len = it.q_len;
+    const int kv_len = it.kv_len;
     const int off = kv_len - q_len;            // query row i sees keys 0 .. i + off
     const int q0 = it.q_tile * BM;
     const int q_last = min(q0 + BM, q_len) - 1;
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
     const int rs32 = a.row_stride;             // bytes between consecutive tokens of this layer
     // contiguous KV: one base per request; paged comparison variant: only the head offset, the block comes per tile
     const bool paged = a.block_table != nullptr;
-    const int64_t sub = (paged ? 0 : static_cast<int64_t>(a.reqids[req]) * a.S) + static_cast<int64_t>(it.kvh) * G::RB;
+    const int64_t sub = (paged ? 0 : static_cast<int64_t>(it.reqid) * a.S) + static_cast<int64_t>(it.kvh) * G::RB;
     const char* kp = a.k_base + sub;
     const char* vp = a.v_base + sub;
     const char* kn = nullptr;

@@ -14,7 +14,9 @@
 
 namespace vattn {
 
-struct PrefillItem { int32_t req; int32_t kvh; int32_t q_tile; int32_t pad; };
+// What a workgroup needs to start on a work item, in one 32-byte record (one scalar load): the batch slot, the
+// KV head, the query tile, and the request's reqId, first query row, chunk length and context length.
+struct PrefillItem { int32_t req; int32_t kvh; int32_t q_tile; int32_t reqid; int32_t q_begin; int32_t q_len; int32_t kv_len; int32_t pad; };
 
 struct PrefillQueues {
     int waves;                        // default kernel: waves per workgroup (8 or 12)
@@ -25,7 +27,8 @@ struct PrefillQueues {
 
 // Default kernel: twelve waves (384 rows per work item, three waves per SIMD) when that still leaves every
 // CU several work items, else eight waves (256 rows).  The wide kernel always takes 256 rows.
-inline PrefillQueues make_prefill_queues(const int32_t* cu_q, const int64_t* kv_lens, int n, int Hq, int H, int num_cus, bool wide) {
+// reqids may be null (paged comparison variant: the record then carries 0).
+inline PrefillQueues make_prefill_queues(const int32_t* reqids, const int32_t* cu_q, const int64_t* kv_lens, int n, int Hq, int H, int num_cus, bool wide) {
     PrefillQueues out{};
     out.waves = 8;
     if (!wide) {
@@ -46,7 +49,7 @@ inline PrefillQueues make_prefill_queues(const int32_t* cu_q, const int64_t* kv_
             const int64_t visible = std::min<int64_t>(static_cast<int64_t>(t + 1) * BM, ql) + off;
             for (int kvh = 0; kvh < H; ++kvh) {
                 const int x = (kvh * nsplit + t % nsplit + ((H * nsplit) % 8 ? r : 0)) & 7;
-                queues[x].push_back(Cost{PrefillItem{r, kvh, t, 0}, visible});
+                queues[x].push_back(Cost{PrefillItem{r, kvh, t, reqids ? reqids[r] : 0, cu_q[r], ql, static_cast<int32_t>(kv_lens[r]), 0}, visible});
             }
         }
     }
@@ -56,7 +59,7 @@ inline PrefillQueues make_prefill_queues(const int32_t* cu_q, const int64_t* kv_
         per_xcd = std::max(per_xcd, qx.size());
     }
     out.per_xcd = static_cast<int>(per_xcd);
-    out.items.assign(per_xcd * 8, PrefillItem{-1, 0, 0, 0});
+    out.items.assign(per_xcd * 8, PrefillItem{-1, 0, 0, 0, 0, 0, 0, 0});
     for (int x = 0; x < 8; ++x)
         for (size_t j = 0; j < queues[x].size(); ++j) out.items[x * per_xcd + j] = queues[x][j].it;
     return out;

@@ -2,7 +2,8 @@
 //   chunk_tokens resident segments_per_slot w0 .. w7 len0 len1 ...
 //       -> total_tiles num_segs max_segs period pre0 .. pre8
 //   Q Hq H num_cus wide n q_len0 kv_len0 q_len1 kv_len1 ...
-//       -> waves rows_per_item per_xcd, then 8 * per_xcd triples req kvh q_tile (queue-major)
+//       -> waves rows_per_item per_xcd, then 8 * per_xcd records req kvh q_tile reqid q_begin q_len kv_len (queue-major;
+//          batch slot r is given reqId 1000 + 7 r)
 #include <cstdio>
 #include <iostream>
 #include <sstream>
@@ -23,9 +24,11 @@ int main() {
             std::vector<int32_t> cu(1, 0);
             std::vector<int64_t> kv;
             for (int r = 0; r < n; ++r) { int q; long long k; in >> q >> k; cu.push_back(cu.back() + q); kv.push_back(k); }
-            const vattn::PrefillQueues pq = vattn::make_prefill_queues(cu.data(), kv.data(), n, Hq, H, cus, wide != 0);
+            std::vector<int32_t> ids;
+            for (int r = 0; r < n; ++r) ids.push_back(1000 + 7 * r);   // reqIds the records must carry
+            const vattn::PrefillQueues pq = vattn::make_prefill_queues(ids.data(), cu.data(), kv.data(), n, Hq, H, cus, wide != 0);
             std::printf("%d %d %d", pq.waves, pq.rows_per_item, pq.per_xcd);
-            for (const auto& it : pq.items) std::printf(" %d %d %d", it.req, it.kvh, it.q_tile);
+            for (const auto& it : pq.items) std::printf(" %d %d %d %d %d %d %d", it.req, it.kvh, it.q_tile, it.reqid, it.q_begin, it.q_len, it.kv_len);
             std::printf("\n");
             std::fflush(stdout);
             continue;

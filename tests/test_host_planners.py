@@ -33,7 +33,7 @@ def planner():
         p.stdin.write(" ".join(str(x) for x in ["Q", Hq, H, cus, int(wide), len(q_lens), *flat]) + "\n")
         p.stdin.flush()
         v = [int(x) for x in p.stdout.readline().split()]
-        items = np.array(v[3:], dtype=np.int64).reshape(8, v[2], 3) if v[2] else np.zeros((8, 0, 3), dtype=np.int64)
+        items = np.array(v[3:], dtype=np.int64).reshape(8, v[2], 7) if v[2] else np.zeros((8, 0, 7), dtype=np.int64)
         return {"waves": v[0], "rows": v[1], "per_xcd": v[2], "items": items}
 
     ask.queues = queues
@@ -144,8 +144,11 @@ def test_prefill_queues_hold_every_work_item_once(planner, Hq, H, wide):
             queue = pq["items"][x]
             live = queue[queue[:, 0] >= 0]
             assert np.all(queue[len(live):, 0] == -1)                     # padding only at the tail
-            seen += [tuple(int(v) for v in it) for it in live]
-            cost = [min((t + 1) * BM, q_lens[r]) + kv_lens[r] - q_lens[r] for r, _, t in live]
+            seen += [tuple(int(v) for v in it[:3]) for it in live]
+            cu = np.concatenate([[0], np.cumsum(q_lens)])
+            for r, _, _, reqid, q_begin, q_len, kv_len in live:              # the record carries the request's own figures
+                assert (reqid, q_begin, q_len, kv_len) == (1000 + 7 * r, cu[r], q_lens[r], kv_lens[r])
+            cost = [min((t + 1) * BM, q_lens[r]) + kv_lens[r] - q_lens[r] for r, _, t in live[:, :3]]
             assert all(a >= b for a, b in zip(cost, cost[1:]))            # longest first
         assert len(seen) == len(want) and set(seen) == want
         assert pq["per_xcd"] * 8 >= len(want) and (pq["per_xcd"] == 0) == (len(want) == 0)
@@ -156,12 +159,12 @@ def test_prefill_queues_keep_a_kv_stream_on_one_xcd(planner):
     pq = planner.queues(32, 8, 256, False, [5000, 9000, 4097], [5000, 9000, 5097])
     home = {}
     for x in range(8):
-        for r, kvh, t in pq["items"][x]:
+        for r, kvh, t in pq["items"][x][:, :3]:
             if r >= 0:
                 assert home.setdefault((int(r), int(kvh)), x) == x
     pq = planner.queues(32, 4, 256, False, [5000, 9000, 4097], [5000, 9000, 5097])       # 4 KV heads: two tile classes each
     home = {}
     for x in range(8):
-        for r, kvh, t in pq["items"][x]:
+        for r, kvh, t in pq["items"][x][:, :3]:
             if r >= 0:
                 assert home.setdefault((int(r), int(kvh), int(t) % 2), x) == x
