@@ -215,7 +215,7 @@ int vattn_attn_decode_append(vattn_ctx* ctx, int layer, void* stream, const void
  * like q; they are NOT in the cache yet.  kv_lens[r] counts them (positions kv_lens[r]-q_len .. kv_lens[r]-1,
  * which step() must already have mapped).  One launch stores the rows into the cache of `layer` and attends;
  * the result equals vattn_append_kv (kv_len_before = kv_lens - q_len) followed by vattn_attn_prefill.  A reqId
- * with a non-empty chunk may appear only once.  Not available with VATTN_FLAG_TENSOR_SLICING (returns -1). */
+ * with a non-empty chunk may appear only once. */
 int vattn_attn_prefill_append(vattn_ctx* ctx, int layer, void* stream, const void* q /*device*/,
                               const void* k_new /*device*/, const void* v_new /*device*/, void* o /*device*/,
                               const int32_t* reqids /*host*/, const int32_t* cu_q /*host*/,

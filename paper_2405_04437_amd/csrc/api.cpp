@@ -401,7 +401,6 @@ int vattn_attn_prefill_append(vattn_ctx* ctx, int layer, void* stream, const voi
     if (!check_ctx_layer(ctx, layer, "attn_prefill_append")) return -1;
     if (n < 0 || (n > 0 && (!q || !k_new || !v_new || !o || !reqids || !cu_q || !kv_lens))) { set_error("attn_prefill_append: null argument"); return -1; }
     if (n == 0) return 0;
-    if (ctx->mem.token_stride() != ctx->mem.T()) { set_error("attn_prefill_append: not available with the tensor-slicing layout"); return -1; }
     if (cu_q[0] != 0) { set_error("attn_prefill_append: cu_q[0] must be 0"); return -1; }
     for (int r = 0; r < n; ++r) {
         const int64_t ql = static_cast<int64_t>(cu_q[r + 1]) - cu_q[r];

@@ -75,7 +75,7 @@ template <int D, int NW> struct PGeo {
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
 // FUSED: the K/V rows of the query tokens arrive in a.k_new / a.v_new and are not in the cache yet.  Tiles at or
-// beyond position kv_len - q_len are read from those arrays (same row stride as the cache), and the first
+// beyond position kv_len - q_len are read from those arrays (rows H*D apart), and the first
 // query head of every group stores the rows of its query tile into the cache; no workgroup ever reads a cache
 // row that this launch writes.
 template <int D, int NW, bool FUSED>
@@ -133,6 +133,8 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
     const char* vp = a.v_base + sub;
     const char* kn = nullptr;
     const char* vn = nullptr;
+    // bytes between consecutive new rows [.., H, D]: the cache's own token stride unless all layers share a buffer
+    const int ns32 = FUSED ? a.H * G::RB : rs32;
     if constexpr (FUSED) {
         // row j of the request's new rows is position off + j of its context
         const int64_t nsub = (static_cast<int64_t>(q_begin) * a.H + it.kvh) * G::RB;
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
             const int nrows = min(q0 + BM, q_len) - q0;
             for (int i = tid; i < nrows * G::CH; i += NW * 64) {
                 const int row = q0 + i / G::CH, c = (i % G::CH) * 16;
-                const int64_t src = static_cast<int64_t>(row) * rs32 + c;
+                const int64_t src = static_cast<int64_t>(row) * ns32 + c;
                 const int64_t dst = static_cast<int64_t>(off + row) * rs32 + c;
                 const u32x4 kx = *reinterpret_cast<const u32x4*>(kn + src);
                 const u32x4 vx = *reinterpret_cast<const u32x4*>(vn + src);
@@ -185,6 +187,8 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
     for (int v = 0; v < 2; ++v)
         dma_voff_k[v] = dma_row * rs32 + (((l % G::CH) ^ G::swz_k((w + v * STEP) * G::RPW + dma_row)) << 4);
     const int dma_voff_v = dma_row * rs32 + (((l % G::CH) ^ G::swz_v(dma_row)) << 4);
+    // (FUSED) the new rows may lie closer together than the cache's tokens: a lane's row offset then shrinks by this much
+    const int dma_row_excess = dma_row * (rs32 - ns32);
     // The loads are written as inline assembly: the compiler does not see them, so its wait-counter pass
     // does not make the LDS reads of tile t wait for the loads of tile t+1 (it cannot tell the two stages
     // apart); the waits that are needed are placed by hand before the barriers.  No other vector-memory
@@ -194,24 +198,41 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
     auto issue_loads = [&](int t) {
         const int tok = t * kBN;
         const int rows = min(kv_len - tok, kBN);   // <= 0 past the end: everything out of range
-        int64_t boff = static_cast<int64_t>(tok) * rs32;
-        const char* kp = kp_cache;
-        const char* vp = vp_cache;
+        const uint32_t kb = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + (t & (G::STAGES - 1)) * G::BUF;   // LDS byte address
         bool straddle = false;   // cache rows up to position off - 1, new rows from there on, in one tile
         if constexpr (FUSED) {
-            if (tok >= off) { kp = kn; vp = vn; boff = static_cast<int64_t>(tok - off) * rs32; }   // a tile of new rows
-            else straddle = tok + kBN > off;
+            if (tok >= off) {
+                // A tile of new rows: same loads from the caller's arrays, whose rows are ns32 bytes apart.
+                const uint32_t nrec = rows > 0 ? static_cast<uint32_t>((rows - 1) * ns32 + G::RB) : 0u;
+                const uint64_t ka = reinterpret_cast<uint64_t>(kn) + static_cast<int64_t>(tok - off) * ns32;
+                const uint64_t va = reinterpret_cast<uint64_t>(vn) + static_cast<int64_t>(tok - off) * ns32;
+                const u32x4 krs = {static_cast<uint32_t>(ka), static_cast<uint32_t>(ka >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
+                const u32x4 vrs = {static_cast<uint32_t>(va), static_cast<uint32_t>(va >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
+#pragma unroll
+                for (int j = 0; j < G::NLW; ++j) {
+                    const int b = w + j * kWaves;
+                    if (b < G::NB) {
+                        const int so = b * G::RPW * ns32;
+                        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                                     :: "s"(kb + b * 1024), "v"(dma_voff_k[((j * kWaves) % PB) / STEP] - dma_row_excess), "s"(krs), "s"(so) : "memory", "m0");
+                        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                                     :: "s"(kb + G::KV + b * 1024), "v"(dma_voff_v - dma_row_excess), "s"(vrs), "s"(so) : "memory", "m0");
+                    }
+                }
+                return;
+            }
+            straddle = tok + kBN > off;
         }
+        int64_t boff = static_cast<int64_t>(tok) * rs32;
         if (paged && rows > 0) {   // block-table lookup; a tile never straddles a block (block_tokens is a multiple of the tile)
             const int blk = a.block_table[static_cast<int64_t>(req) * a.table_stride + tok / a.block_tokens];
             boff = (static_cast<int64_t>(blk) * a.block_tokens + tok % a.block_tokens) * rs32;
         }
         const uint32_t nrec = rows > 0 ? static_cast<uint32_t>((rows - 1) * rs32 + G::RB) : 0u;
-        const uint64_t ka = reinterpret_cast<uint64_t>(kp + boff), va = reinterpret_cast<uint64_t>(vp + boff);
+        const uint64_t ka = reinterpret_cast<uint64_t>(kp_cache + boff), va = reinterpret_cast<uint64_t>(vp_cache + boff);
         // raw buffer resource: base[47:0], stride 0, num_records, data format word
         const u32x4 krs = {static_cast<uint32_t>(ka), static_cast<uint32_t>(ka >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
         const u32x4 vrs = {static_cast<uint32_t>(va), static_cast<uint32_t>(va >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
-        const uint32_t kb = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + (t & (G::STAGES - 1)) * G::BUF;   // LDS byte address
 #pragma unroll
         for (int j = 0; j < G::NLW; ++j) {
             const int b = w + j * kWaves;                 // scalar: which 1 KiB block of the tile
@@ -221,22 +242,24 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void prefill_kernel(PrefillArgs a)
                     if (straddle) {
                         // At most once per work item, and only when `off` is not a multiple of the tile.  Lanes whose
                         // row lies below `off` load from the cache, the others from the new rows (a resource whose
-                        // row 0 is position `tok`, so the same offsets apply); a lane that is switched off writes
-                        // nothing to LDS (checked on the chip), so the two loads fill disjoint parts of the block.
-                        const uint64_t nka = reinterpret_cast<uint64_t>(kn) + static_cast<int64_t>(tok - off) * rs32;
-                        const uint64_t nva = reinterpret_cast<uint64_t>(vn) + static_cast<int64_t>(tok - off) * rs32;
-                        const u32x4 nkrs = {static_cast<uint32_t>(nka), static_cast<uint32_t>(nka >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
-                        const u32x4 nvrs = {static_cast<uint32_t>(nva), static_cast<uint32_t>(nva >> 32) & 0xFFFFu, nrec, static_cast<uint32_t>(kRsrcWord3)};
+                        // row 0 is position `tok`); a lane that is switched off writes nothing to LDS (checked on
+                        // the chip), so the two loads fill disjoint parts of the block.
+                        const uint64_t nka = reinterpret_cast<uint64_t>(kn) + static_cast<int64_t>(tok - off) * ns32;
+                        const uint64_t nva = reinterpret_cast<uint64_t>(vn) + static_cast<int64_t>(tok - off) * ns32;
+                        const uint32_t nnrec = static_cast<uint32_t>((rows - 1) * ns32 + G::RB);
+                        const u32x4 nkrs = {static_cast<uint32_t>(nka), static_cast<uint32_t>(nka >> 32) & 0xFFFFu, nnrec, static_cast<uint32_t>(kRsrcWord3)};
+                        const u32x4 nvrs = {static_cast<uint32_t>(nva), static_cast<uint32_t>(nva >> 32) & 0xFFFFu, nnrec, static_cast<uint32_t>(kRsrcWord3)};
                         if (tok + b * G::RPW + dma_row < off) {
                             asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                                          :: "s"(kb + b * 1024), "v"(dma_voff_k[((j * kWaves) % PB) / STEP]), "s"(krs), "s"(so) : "memory", "m0");
                             asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                                          :: "s"(kb + G::KV + b * 1024), "v"(dma_voff_v), "s"(vrs), "s"(so) : "memory", "m0");
                         } else {
+                            const int nso = b * G::RPW * ns32;
                             asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                                         :: "s"(kb + b * 1024), "v"(dma_voff_k[((j * kWaves) % PB) / STEP]), "s"(nkrs), "s"(so) : "memory", "m0");
+                                         :: "s"(kb + b * 1024), "v"(dma_voff_k[((j * kWaves) % PB) / STEP] - dma_row_excess), "s"(nkrs), "s"(nso) : "memory", "m0");
                             asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                                         :: "s"(kb + G::KV + b * 1024), "v"(dma_voff_v), "s"(nvrs), "s"(so) : "memory", "m0");
+                                         :: "s"(kb + G::KV + b * 1024), "v"(dma_voff_v - dma_row_excess), "s"(nvrs), "s"(nso) : "memory", "m0");
                         }
                         continue;
                     }

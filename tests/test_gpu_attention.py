@@ -330,17 +330,39 @@ def test_prefill_with_fused_append_matches_oracle_and_fills_the_cache(Hq, H, D):
     s.close()
 
 
-def test_prefill_with_fused_append_is_refused_for_the_sliced_layout():
+def test_prefill_with_fused_append_in_the_sliced_layout():
+    """All layers in one buffer: the cache's tokens are N*H*D apart, the caller's new rows H*D; chunks that start on
+    and inside a tile, both layers."""
     import torch
     import paper_2405_04437_amd as P
-    from paper_2405_04437_amd.runtime import KvSession
+    from paper_2405_04437_amd.runtime import KvSession, bits_to_tensor, tensor_to_f32
 
-    shape = W.Shape("t", 8, 2, 64, 2)
-    s = KvSession(8, 2, 64, 2, 256, 8 * MiB, 2, 64 * KiB, flags=P.FLAG_TENSOR_SLICING)
-    r = s.admit(100)
+    shape = W.Shape("t", 8, 2, 64, 3)
+    layers = 3
+    q_lens = [300, 129, 1, 64]
+    offs = [1000, 0, 77, 64]
+    kv_lens = [q + o for q, o in zip(q_lens, offs)]
+    n = len(q_lens)
+    scale = W.softmax_scale(64)
+    G = 64 * KiB
+    per_req = (max(kv_lens) * shape.token_bytes * layers + G - 1) // G * G
+    s = KvSession(8, 2, 64, n, max(kv_lens), per_req * 2 * n, layers, G, flags=P.FLAG_TENSOR_SLICING)
+    ids = [s.admit(L) for L in kv_lens]
     s.step()
-    q = torch.zeros((100, 8, 64), dtype=torch.bfloat16, device="cuda")
-    kv = torch.zeros((100, 2, 64), dtype=torch.bfloat16, device="cuda")
-    assert s.va.attn_prefill_append(0, s.stream, q, kv, kv, torch.empty_like(q), [r], [0, 100], [100], 0.125) == -1
-    assert "slicing" in P.last_error()
+    for layer in (2, 0):
+        inp = W.draw_attention_inputs(shape, q_lens, kv_lens, seed=40 + layer)
+        cu_old = np.zeros(n + 1, dtype=np.int64); cu_old[1:] = np.cumsum(offs)
+        s.append(layer, bits_to_tensor(np.concatenate([k[:o] for k, o in zip(inp.k, offs)])),
+                 bits_to_tensor(np.concatenate([v[:o] for v, o in zip(inp.v, offs)])), ids, cu_old, [0] * n)
+        poison = torch.full((int(inp.cu_q[-1]), 2, 64), float("nan"), dtype=torch.bfloat16, device="cuda")
+        s.append(layer, poison, poison, ids, inp.cu_q, offs)
+        k_new = bits_to_tensor(np.concatenate([k[o:] for k, o in zip(inp.k, offs)]))
+        v_new = bits_to_tensor(np.concatenate([v[o:] for v, o in zip(inp.v, offs)]))
+        q = bits_to_tensor(inp.q)
+        o = torch.empty_like(q)
+        assert s.va.attn_prefill_append(layer, s.stream, q, k_new, v_new, o, ids, inp.cu_q, kv_lens, scale) == 0, P.last_error()
+        want = OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale)
+        check(tensor_to_f32(o), want, f"fused append + prefill, sliced layout, layer {layer}")
+        o2 = s.prefill(layer, q, ids, inp.cu_q, kv_lens, scale)       # the cache holds the rows now
+        assert torch.equal(o.view(torch.int16), o2.view(torch.int16))
     s.close()
