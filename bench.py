@@ -362,6 +362,11 @@ def main() -> int:
             out["cpu_baseline"] = r.pop("cpu_baseline")
         out["decode_detail"] = {k: r[k] for k in ("reduce_ms", "tokens_in_batch", "map_calls_in_timed_region",
                                                   "map_us_in_timed_region", "unmap_calls_in_timed_region")}
+        # what a read-only kernel of the same launch shape gets out of HBM (4 GiB, best of three launches)
+        import paper_2405_04437_amd as P
+        stream = P.stream_microbench(4 << 30)
+        out["roofline"]["sustained_read_gbs"] = stream
+        out["roofline"]["frac_of_sustained_read"] = r["gbs_kernel"] / stream
         if args.only == "all":
             # the same batch with a host synchronisation after every single layer's attention: the
             # cost of the per-iteration host work when nothing amortises it

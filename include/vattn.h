@@ -167,6 +167,13 @@ int vattn_vmm_microbench(int device, int64_t bytes, int count, double* out_us /*
  * context; allocates and frees a few KiB of device memory; synchronises the device. */
 int vattn_mfma_microbench(int device, int normal_operands, int rounds, double* out /*host, 2 values*/);
 
+/* Streaming-read micro-benchmark for the roofline of the decode kernel (which reads every K/V byte once, Sec. 7.2
+ * calls it memory-bound): one workgroup of four waves per CU reads its contiguous share of a `bytes`-sized buffer
+ * with 16-byte non-temporal loads, 16 per lane in flight - the decode kernel's launch shape and load pattern
+ * without its arithmetic.  *out_gbs = best of three launches, GB/s.  Needs no context; allocates and frees the
+ * buffer (64 MiB .. 64 GiB); synchronises the device. */
+int vattn_stream_microbench(int device, int64_t bytes, double* out_gbs /*host*/);
+
 /* ---- the attention path (Eq. 2 of the paper, evaluated per request) -------------------------- */
 
 /* KV append ("a single tensor copy", Sec. 7.1): copies the new rows k_new/v_new [sum q_len, H, D]

@@ -77,12 +77,13 @@ def _load() -> ctypes.CDLL:
     lib.vattn_sync.argtypes = [vp]
     lib.vattn_vmm_microbench.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, dp]
     lib.vattn_mfma_microbench.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, dp]
+    lib.vattn_stream_microbench.argtypes = [ctypes.c_int, ctypes.c_int64, dp]
     for name in ("vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_query",
                  "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill", "vattn_attn_decode",
                  "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide",
                  "vattn_step_counters", "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
                  "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights",
-                 "vattn_mfma_microbench"):
+                 "vattn_mfma_microbench", "vattn_stream_microbench"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -95,7 +96,7 @@ EXPORTED = ["vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqi
             "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide", "vattn_step_counters",
             "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
             "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights",
-            "vattn_mfma_microbench", "vattn_last_error"]
+            "vattn_mfma_microbench", "vattn_stream_microbench", "vattn_last_error"]
 
 
 def last_error() -> str:
@@ -289,3 +290,11 @@ def mfma_microbench(normal_operands: bool, rounds: int = 100000, device: int = 0
     if lib.vattn_mfma_microbench(device, 1 if normal_operands else 0, rounds, out) != 0:
         raise VattnError("vattn_mfma_microbench: " + last_error())
     return out[0], out[1]
+
+
+def stream_microbench(nbytes: int = 4 << 30, device: int = 0) -> float:
+    """GB/s of a kernel that only reads `nbytes` from HBM in the decode kernel's launch shape (see vattn.h)."""
+    out = (ctypes.c_double * 1)()
+    if lib.vattn_stream_microbench(device, nbytes, out) != 0:
+        raise VattnError("vattn_stream_microbench: " + last_error())
+    return out[0]

@@ -130,6 +130,10 @@ int vattn_vmm_microbench(int device, int64_t bytes, int count, double* out_us) {
     return vmm_microbench(device, bytes, count, out_us) ? 0 : -1;
 }
 
+int vattn_stream_microbench(int device, int64_t bytes, double* out_gbs) {
+    return stream_microbench(device, bytes, out_gbs) ? 0 : -1;
+}
+
 int vattn_mfma_microbench(int device, int normal_operands, int rounds, double* out) {
     if (!out) { set_error("mfma_microbench: null output"); return -1; }
     return mfma_microbench(device, normal_operands != 0, rounds, &out[0], &out[1]) ? 0 : -1;

@@ -1,4 +1,4 @@
-// Matrix-pipe micro-benchmark: what dense bf16 rate the chip sustains with nothing else going on.
+// Micro-benchmarks of the two roofs.  Matrix pipes: what dense bf16 rate the chip sustains with nothing else going on.
 //
 // Every wave runs rounds of four independent v_mfma_f32_32x32x16_bf16 whose operands stay in registers
 // (no LDS, no memory traffic inside the timed loop), two waves per SIMD on every CU.  With all-zero
@@ -53,7 +53,58 @@ __global__ __launch_bounds__(kWavesPerGroup * 64) void mfma_loop_kernel(const u3
     if (threadIdx.x == 0) { clocks[blockIdx.x * 2] = c1 - c0; clocks[blockIdx.x * 2 + 1] = w1 - w0; }
 }
 
+// Streaming-read micro-benchmark: what HBM delivers to a kernel that only reads.  One workgroup of four waves per
+// CU walks its own contiguous share of the buffer with 16-byte non-temporal loads, 16 per lane in flight - the
+// launch shape and load pattern of the decode kernel without its arithmetic.
+constexpr int kStreamUnroll = 16;
+__global__ __launch_bounds__(kWavesPerGroup * 64) void stream_read_kernel(const u32x4* src, size_t vec_per_group, uint32_t* sink) {
+    const u32x4* p = src + static_cast<size_t>(blockIdx.x) * vec_per_group + threadIdx.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const size_t rounds = vec_per_group / (kWavesPerGroup * 64 * kStreamUnroll);
+    for (size_t r = 0; r < rounds; ++r) {
+        u32x4 v[kStreamUnroll];
+#pragma unroll
+        for (int i = 0; i < kStreamUnroll; ++i) v[i] = __builtin_nontemporal_load(p + static_cast<size_t>(i) * kWavesPerGroup * 64);
+#pragma unroll
+        for (int i = 0; i < kStreamUnroll; ++i) acc ^= v[i];
+        p += static_cast<size_t>(kStreamUnroll) * kWavesPerGroup * 64;
+    }
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u) sink[blockIdx.x] = acc[0];   // keeps the loads alive; practically never taken
+}
+
 }  // namespace
+
+bool stream_microbench(int device, int64_t bytes, double* gbs) {
+    if (bytes < (64 << 20) || bytes > (int64_t{64} << 30) || !gbs) { set_error("stream_microbench: size must be between 64 MiB and 64 GiB"); return false; }
+    if (!hip_ok(hipSetDevice(device), "hipSetDevice")) return false;
+    int cus = 0;
+    if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device), "hipDeviceGetAttribute")) return false;
+    const size_t round_vecs = static_cast<size_t>(kWavesPerGroup) * 64 * kStreamUnroll;                 // 16-byte vectors per round
+    const size_t vec_per_group = static_cast<size_t>(bytes) / 16 / static_cast<size_t>(cus) / round_vecs * round_vecs;
+    const size_t total = vec_per_group * static_cast<size_t>(cus) * 16;
+    u32x4* buf = nullptr; uint32_t* sink = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    bool ok = hip_ok(hipMalloc(reinterpret_cast<void**>(&buf), total), "hipMalloc") &&
+              hip_ok(hipMalloc(reinterpret_cast<void**>(&sink), static_cast<size_t>(cus) * 4), "hipMalloc") &&
+              hip_ok(hipMemset(buf, 0x5A, total), "hipMemset") &&
+              hip_ok(hipEventCreate(&e0), "hipEventCreate") && hip_ok(hipEventCreate(&e1), "hipEventCreate");
+    float best = 0.f;
+    for (int rep = 0; ok && rep < 4; ++rep) {   // the first launch warms up; the best of the rest counts
+        ok = hip_ok(hipEventRecord(e0, nullptr), "hipEventRecord");
+        if (!ok) break;
+        stream_read_kernel<<<cus, kWavesPerGroup * 64>>>(buf, vec_per_group, sink);
+        float ms = 0.f;
+        ok = hip_ok(hipEventRecord(e1, nullptr), "hipEventRecord") && hip_ok(hipDeviceSynchronize(), "hipDeviceSynchronize") &&
+             hip_ok(hipGetLastError(), "stream_read_kernel") && hip_ok(hipEventElapsedTime(&ms, e0, e1), "hipEventElapsedTime");
+        if (ok && rep > 0 && (best == 0.f || ms < best)) best = ms;
+    }
+    if (ok) *gbs = static_cast<double>(total) / (static_cast<double>(best) * 1e6);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (buf) (void)hipFree(buf);
+    if (sink) (void)hipFree(sink);
+    return ok;
+}
 
 bool mfma_microbench(int device, bool normal_operands, int rounds, double* tflops, double* shader_mhz) {
     if (rounds < 1 || rounds > 10000000 || !tflops || !shader_mhz) { set_error("mfma_microbench: invalid argument"); return false; }

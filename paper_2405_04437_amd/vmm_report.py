@@ -444,7 +444,7 @@ def fused_append(P, torch, W, quick):
 
 
 def matrix_pipe(P):
-    print("## 9. What the matrix pipes sustain: register-only MFMA loop, two waves per SIMD on every CU\n")
+    print("## 9. What the two roofs sustain: a register-only MFMA loop and a read-only stream\n")
     print("`v_mfma_f32_32x32x16_bf16`, operands in registers, no LDS or memory traffic in the timed loop; shader clock read")
     print("inside the kernel (cycle counter / 100 MHz counter).  N(0,1) is the value distribution of the attention workloads.\n")
     print("| operands | dense bf16 TFLOP/s | shader clock MHz | fraction of the 2.5 PFLOP/s peak |")
@@ -452,6 +452,14 @@ def matrix_pipe(P):
     for name, normal in (("all zero", False), ("N(0,1)", True)):
         best = max(P.mfma_microbench(normal, 200000) for _ in range(3))
         print(f"| {name} | {best[0]:.0f} | {best[1]:.0f} | {best[0] / 2500:.2f} |")
+    print()
+    print("And what HBM delivers to a kernel that only reads: one workgroup of four waves per CU, each a contiguous share,")
+    print("16-byte non-temporal loads, 16 per lane in flight (the decode kernel's launch shape without its arithmetic).\n")
+    print("| buffer | GB/s | fraction of the 8 TB/s peak |")
+    print("|---|---|---|")
+    for gib in (1, 4, 16):
+        g = P.stream_microbench(gib << 30)
+        print(f"| {gib} GiB | {g:.0f} | {g / 8000:.2f} |")
     print()
 
 

@@ -235,3 +235,13 @@ def test_mfma_microbench_reports_rate_and_clock():
     assert 500 < cn <= cz * 1.02 and cz < 2600, (cz, cn)
     with pytest.raises(P.VattnError):
         P.mfma_microbench(True, 0)
+
+
+def test_stream_microbench_reports_a_plausible_bandwidth():
+    """The streaming-read micro-benchmark: between a tenth of the HBM peak and the peak itself; bad sizes refused."""
+    import paper_2405_04437_amd as P
+
+    gbs = P.stream_microbench(1 << 30)
+    assert 800 < gbs < 8000, gbs
+    with pytest.raises(P.VattnError):
+        P.stream_microbench(1 << 20)
