@@ -35,8 +35,8 @@ extern "C" {
 
 typedef struct vattn_ctx vattn_ctx; /* opaque */
 
-/* Policy for what free_reqid does with a request's pages (Sec. 5.3.4 "may unmap the physical
- * pages of a completed request or defer them", Sec. 6.1.2 deferred reclamation). */
+/* Policy for what free_reqid does with a finished request's page-groups: unmap them at once, or keep
+ * them mapped for later reuse or reclamation (Sec. 5.3.4; deferred reclamation, Sec. 6.1.2). */
 #define VATTN_POLICY_SYNC_UNMAP 0u /* free_reqid unmaps everything at once                      */
 #define VATTN_POLICY_DEFERRED 1u   /* pages stay mapped; alloc_reqid prefers the best-backed id;
                                       step() reclaims from inactive ids only when the pool is short */
@@ -107,9 +107,12 @@ int vattn_destroy(vattn_ctx* ctx);
 int vattn_alloc_reqid(vattn_ctx* ctx);
 
 /* free_reqid (Table 4; Sec. 5.3.4): marks reqId inactive.  SYNC_UNMAP: also unmaps all its
- * page-groups in all 2N buffers and returns them to the pool - the caller must make sure no
- * enqueued kernel still reads them.  DEFERRED: leaves them mapped.  -1 if reqid is out of range or
- * not active. */
+ * page-groups in all 2N buffers and returns them to the pool.  DEFERRED: leaves them mapped; a later
+ * step() or background pass may take them back.  Under every policy, call it only once the last
+ * kernel that reads or writes the request's KV has FINISHED (not merely been enqueued): its pages may
+ * be unmapped at any time afterwards.  (step() on the caller's thread additionally waits for the
+ * device before it reclaims from inactive ids; SYNC_UNMAP and background passes do not wait.)
+ * -1 if reqid is out of range or not active. */
 int vattn_free_reqid(vattn_ctx* ctx, int reqid);
 
 /* step (Table 4; Sec. 5.3.3): seq_lens[count], count == B, holds the context length of every
@@ -117,7 +120,10 @@ int vattn_free_reqid(vattn_ctx* ctx, int reqid);
  * ceil(len*H*D*P / page_group_bytes) page-groups mapped, contiguously from its base, in each of the
  * 2N buffers.  All-or-nothing: if the pool (plus, under DEFERRED, pages held by inactive ids)
  * cannot cover the demand, or an argument is invalid (wrong count, len > L, non-zero length for an
- * inactive id), it returns -1 and changes nothing.  Lengths that shrink never unmap. */
+ * inactive id), it returns -1 and changes nothing.  If a driver call fails halfway, everything this
+ * call mapped is unmapped again, page-groups it took back from inactive ids are mapped back (they stay
+ * in the pool if the driver refuses that as well), and -1 is returned: the mapped counts of the active
+ * requests are those at entry.  Lengths that shrink never unmap. */
 int vattn_step(vattn_ctx* ctx, const int64_t* seq_lens /*host*/, int count);
 
 /* Request-level indexing (Sec. 5.2.3): device address of reqId's sub-tensor in layer `layer`,
@@ -150,33 +156,9 @@ int vattn_step_counters(vattn_ctx* ctx, int64_t* sync_map_calls, int64_t* backgr
  * themselves; exposed so that measurements can separate the pass from what follows. */
 int vattn_sync(vattn_ctx* ctx);
 
-/* Per-call latency of the HIP virtual-memory API at one page-group size (the analogue of Table 3 of
- * the paper): creates, maps, touches and tears down `count` page-groups of `bytes` each on `device`
- * and writes average microseconds per call to out_us[9] (host):
- *   0 hipMemAddressReserve   1 hipMemCreate   2 hipMemMap   3 hipMemSetAccess (one page-group per call)
- *   4 hipMemSetAccess, ONE call over all page-groups freshly mapped again (total)   5 hipMemUnmap   6 hipMemRelease
- *   7 hipMemAddressFree      8 a kernel writing every mapped byte once (total).
- * Needs no context.  `bytes` must be a multiple of the allocation granularity. */
-int vattn_vmm_microbench(int device, int64_t bytes, int count, double* out_us /*host*/);
-
-/* Matrix-pipe micro-benchmark for the roofline of the prefill kernel (the bf16 contractions of Eq. 2): two
- * waves per SIMD on every CU run `rounds` rounds of four independent v_mfma_f32_32x32x16_bf16 with operands
- * held in registers.  normal_operands = 0: all-zero operands (the chip keeps its full clock); 1: N(0,1)
- * operands, the value distribution of the workloads here (the chip lowers its clock to hold its power limit).
- * out[0] = dense TFLOP/s over the launch, out[1] = shader clock in MHz seen inside the kernel.  Needs no
- * context; allocates and frees a few KiB of device memory; synchronises the device. */
-int vattn_mfma_microbench(int device, int normal_operands, int rounds, double* out /*host, 2 values*/);
-
-/* Streaming-read micro-benchmark for the roofline of the decode kernel (which reads every K/V byte once, Sec. 7.2
- * calls it memory-bound): one workgroup of four waves per CU reads its contiguous share of a `bytes`-sized buffer
- * with 16-byte non-temporal loads, 16 per lane in flight - the decode kernel's launch shape and load pattern
- * without its arithmetic.  *out_gbs = best of three launches, GB/s.  Needs no context; allocates and frees the
- * buffer (64 MiB .. 64 GiB); synchronises the device. */
-int vattn_stream_microbench(int device, int64_t bytes, double* out_gbs /*host*/);
-
 /* ---- the attention path (Eq. 2 of the paper, evaluated per request) -------------------------- */
 
-/* KV append ("a single tensor copy", Sec. 7.1): copies the new rows k_new/v_new [sum q_len, H, D]
+/* KV append (Sec. 7.1: with contiguous KV the append is one plain copy): copies the new rows k_new/v_new [sum q_len, H, D]
  * (device, bf16) of n requests to token positions kv_len_before[r] .. kv_len_before[r]+q_len-1 of
  * each request's K and V sub-tensor in `layer`.  cu_q[n+1] are prefix sums of q_len.  The target
  * range must already be mapped by step(). */
@@ -188,7 +170,8 @@ int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new /
  * order; kv_lens[r] is the context length AFTER the q_len newest tokens were appended, so query
  * row i of request r attends to keys 0 .. kv_lens[r]-q_len+i (a chunk appended to an existing
  * context sees all of it).  Query head h reads KV head h/(Hq/H).  scores are multiplied by `scale`
- * (Eq. 2 divides by "scale"; pass 1/sqrt(D)).  reqids[r] selects the KV sub-tensor of batch slot r
+ * (Eq. 2 divides by a constant; pass its reciprocal, 1/sqrt(D) in all workloads here; it must be finite
+ * and > 0 in every attention call, else -1).  reqids[r] selects the KV sub-tensor of batch slot r
  * (the batch-index indirection of Sec. 5.3.4).  fp32 accumulation, bf16 output. */
 int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q /*device*/,
                        void* o /*device*/, const int32_t* reqids /*host*/, const int32_t* cu_q /*host*/,
@@ -207,8 +190,8 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q /*d
                       void* o /*device*/, const int32_t* reqids /*host*/, const int64_t* kv_lens /*host*/,
                       int n, float scale, void* workspace /*device*/, size_t workspace_bytes);
 
-/* Decode attention with the KV append fused in (the "kvcache append inside the attention kernel" of
- * Sec. 7.1): k_new, v_new [n, H, D] bf16 (device) are the K/V rows of each request's NEWEST token;
+/* Decode attention with the KV append fused in (Sec. 7.1 names kernels that write the new K/V rows
+ * themselves): k_new, v_new [n, H, D] bf16 (device) are the K/V rows of each request's NEWEST token;
  * kv_lens[r] counts that token (it is position kv_lens[r]-1, which step() must already have mapped).
  * The kernel stores the rows into the cache of `layer` and attends over all kv_lens[r] tokens; the
  * result equals vattn_append_kv followed by vattn_attn_decode.  A reqId may appear only once. */
@@ -217,8 +200,7 @@ int vattn_attn_decode_append(vattn_ctx* ctx, int layer, void* stream, const void
                              const int32_t* reqids /*host*/, const int64_t* kv_lens /*host*/, int n, float scale,
                              void* workspace /*device*/, size_t workspace_bytes);
 
-/* Prefill with the KV append fused in (the second half of the "fused append" the paper's Sec. 7.1 leaves as
- * a separate copy).  k_new, v_new: [sum q_len, H, D] bf16 (device), the K/V rows of the query tokens, packed
+/* Prefill with the KV append fused in (which the paper's Sec. 7.1 leaves as a separate copy).  k_new, v_new: [sum q_len, H, D] bf16 (device), the K/V rows of the query tokens, packed
  * like q; they are NOT in the cache yet.  kv_lens[r] counts them (positions kv_lens[r]-q_len .. kv_lens[r]-1,
  * which step() must already have mapped).  One launch stores the rows into the cache of `layer` and attends;
  * the result equals vattn_append_kv (kv_len_before = kv_lens - q_len) followed by vattn_attn_prefill.  A reqId
@@ -271,13 +253,6 @@ int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* laun
 int vattn_set_decode_chunk(vattn_ctx* ctx, int tokens);
 int vattn_set_decode_tuning(vattn_ctx* ctx, int segments_per_slot);
 int vattn_set_decode_xcd_weights(vattn_ctx* ctx, const float* weights /*host, 8 values, or NULL*/);
-
-/* Selects the prefill kernel, one workgroup per CU in both cases:
- * 0 (default) = waves of 32 query rows, twelve per workgroup (384 rows) when the launch has many work
- * items, else eight (256 rows); 1 = four waves of 64 rows, every K/V fragment read from LDS feeds two
- * matrix instructions, software-pipelined (measured slower).  Same results up to floating-point
- * summation order. */
-int vattn_set_prefill_wide(vattn_ctx* ctx, int enabled);
 
 const char* vattn_last_error(void);
 

@@ -45,7 +45,7 @@ Extensions beyond the base design (each switched on by a constructor argument):
        back, ascending id, highest page-group first, until the threshold is met;
     3. eager allocation (Sec. 6.1.2, "deferred" only): the inactive id alloc_reqid would return
        next is topped up to `eager_page_groups`, as far as whole rows fit the free pool.
-  The paper leaves the amounts open ("a certain number", "e.g. less than 10%"): they are parameters.
+  The paper leaves the amounts open (it names no count and gives 10 % only as an example): they are parameters.
 
 Parity status: pinned against the figures the paper prints (tokens per page-group table, per-token
 footprints, the 120-calls-per-request-page example, the five-panel walk-through of the design

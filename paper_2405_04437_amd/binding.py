@@ -72,7 +72,6 @@ def _load() -> ctypes.CDLL:
     lib.vattn_set_decode_chunk.argtypes = [vp, ctypes.c_int]
     lib.vattn_set_decode_tuning.argtypes = [vp, ctypes.c_int]
     lib.vattn_set_decode_xcd_weights.argtypes = [vp, ctypes.c_void_p]
-    lib.vattn_set_prefill_wide.argtypes = [vp, ctypes.c_int]
     lib.vattn_step_counters.argtypes = [vp, i64p, i64p, dp, dp, dp]
     lib.vattn_sync.argtypes = [vp]
     lib.vattn_vmm_microbench.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, dp]
@@ -80,7 +79,7 @@ def _load() -> ctypes.CDLL:
     lib.vattn_stream_microbench.argtypes = [ctypes.c_int, ctypes.c_int64, dp]
     for name in ("vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_query",
                  "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill", "vattn_attn_decode",
-                 "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide",
+                 "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning",
                  "vattn_step_counters", "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
                  "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights",
                  "vattn_mfma_microbench", "vattn_stream_microbench"):
@@ -93,7 +92,7 @@ lib = _load()
 EXPORTED = ["vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqid", "vattn_step", "vattn_kv_ptr",
             "vattn_query", "vattn_stats", "vattn_counters", "vattn_append_kv", "vattn_attn_prefill",
             "vattn_decode_workspace_bytes", "vattn_attn_decode", "vattn_set_timing", "vattn_kernel_time",
-            "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_set_prefill_wide", "vattn_step_counters",
+            "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_step_counters",
             "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
             "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights",
             "vattn_mfma_microbench", "vattn_stream_microbench", "vattn_last_error"]
@@ -260,9 +259,6 @@ class Vattn:
 
     def set_decode_chunk(self, tokens: int) -> int:
         return lib.vattn_set_decode_chunk(self._h, tokens)
-
-    def set_prefill_wide(self, enabled: bool) -> int:
-        return lib.vattn_set_prefill_wide(self._h, 1 if enabled else 0)
 
     def set_decode_tuning(self, segments_per_slot: int) -> int:
         return lib.vattn_set_decode_tuning(self._h, segments_per_slot)

@@ -8,17 +8,14 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvattn.so")
-SOURCES = ["kv_memory.cpp", "hip_support.cpp", "api.cpp", "kv_append.hip", "attn_decode.hip", "attn_prefill.hip", "attn_prefill_wide.hip", "mfma_probe.hip"]
+SOURCES = ["kv_memory.cpp", "hip_support.cpp", "api.cpp", "kv_append.hip", "attn_decode.hip", "attn_prefill.hip", "mfma_probe.hip"]
 # Packed-fp32 instruction selection is switched off for all device code (known to misbehave on the
 # target machines); the host pass does not know the feature and warns, which is harmless.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-# The wide prefill kernel keeps its score accumulators in architectural registers (the softmax reads
-# them with vector instructions); without this the compiler parks them in accumulation registers and
-# copies every value back.
-EXTRA = {"attn_prefill_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+EXTRA = {}   # per-file extra compiler flags
 
 
 def build(verbose: bool = False) -> str:

@@ -2,6 +2,7 @@
 // attention path runs in the HIP kernels; this file only validates, packs index arrays into a pinned
 // staging slot, uploads them on the caller's stream and launches.
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <new>
 
@@ -32,6 +33,14 @@ bool check_request(vattn_ctx* ctx, int reqid, int64_t kv_len, const char* fn) {
         return false;
     }
     return true;
+}
+
+// Eq. 2 divides the scores by a positive constant; the kernels multiply by `scale` and rely on its sign (the
+// prefill kernel takes row maxima before scaling).  Zero, negative, infinite or NaN values are refused.
+bool check_scale(float scale, const char* fn) {
+    if (std::isfinite(scale) && scale > 0.f) return true;
+    set_error(std::string(fn) + ": scale must be finite and > 0");
+    return false;
 }
 
 DecodePlan plan_decode(const vattn_ctx* ctx, const int64_t* kv_lens, int n) {
@@ -174,7 +183,8 @@ int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new, 
     a.reqids = reinterpret_cast<const int32_t*>(d);
     a.kv_before = reinterpret_cast<const int32_t*>(d + off_kv);
     a.cu_q = reinterpret_cast<const int32_t*>(d + off_cu);
-    return launch_append_kv(a, nullptr, s) ? 0 : -1;
+    const bool ok = launch_append_kv(a, nullptr, s);
+    return ctx->ring.release(s) && ok ? 0 : -1;
 }
 
 int64_t vattn_decode_workspace_bytes(vattn_ctx* ctx, const int64_t* kv_lens, int n) {
@@ -262,10 +272,13 @@ int decode_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* 
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + part_o_bytes);
     const InlineMeta* imp = inl ? &im : nullptr;
     LaunchEvents ev_split, ev_reduce;
-    if (ctx->timing && (!ctx->timers[0].next(&ev_split.start, &ev_split.stop) || !ctx->timers[2].next(&ev_reduce.start, &ev_reduce.stop))) return -1;
-    if (!launch_decode_splitk(a, imp, s, ev_split)) return -1;
-    if (!launch_decode_reduce(a, imp, s, ev_reduce)) return -1;
-    return 0;
+    if (ctx->timing && (!ctx->timers[0].next(&ev_split.start, &ev_split.stop) || !ctx->timers[2].next(&ev_reduce.start, &ev_reduce.stop))) {
+        if (!inl) (void)ctx->ring.release(s);
+        return -1;
+    }
+    const bool ok = launch_decode_splitk(a, imp, s, ev_split) && launch_decode_reduce(a, imp, s, ev_reduce);
+    if (!inl && !ctx->ring.release(s)) return -1;   // the staging slot stays taken until both kernels have read it
+    return ok ? 0 : -1;
 }
 
 }  // namespace
@@ -274,6 +287,7 @@ extern "C" {
 
 int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
                       const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes) {
+    if (!check_scale(scale, "attn_decode")) return -1;
     if (!check_ctx_layer(ctx, layer, "attn_decode")) return -1;
     if (n < 0 || (n > 0 && (!q || !o || !reqids || !kv_lens || !workspace))) { set_error("attn_decode: null argument"); return -1; }
     if (n == 0) return 0;
@@ -286,6 +300,7 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, vo
 
 int vattn_attn_decode_append(vattn_ctx* ctx, int layer, void* stream, const void* q, const void* k_new, const void* v_new, void* o,
                              const int32_t* reqids, const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes) {
+    if (!check_scale(scale, "attn_decode_append")) return -1;
     if (!check_ctx_layer(ctx, layer, "attn_decode_append")) return -1;
     if (n < 0 || (n > 0 && (!q || !k_new || !v_new || !o || !reqids || !kv_lens || !workspace))) { set_error("attn_decode_append: null argument"); return -1; }
     if (n == 0) return 0;
@@ -302,6 +317,7 @@ int vattn_attn_decode_append(vattn_ctx* ctx, int layer, void* stream, const void
 int vattn_attn_decode_paged(vattn_ctx* ctx, void* stream, const void* q, void* o, const void* k_pool, const void* v_pool,
                             int64_t num_blocks, int block_tokens, const int32_t* block_table, int max_blocks_per_req,
                             const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes) {
+    if (!check_scale(scale, "attn_decode_paged")) return -1;
     if (!ctx) { set_error("attn_decode_paged: null context"); return -1; }
     if (n < 0 || (n > 0 && (!q || !o || !k_pool || !v_pool || !block_table || !kv_lens || !workspace))) { set_error("attn_decode_paged: null argument"); return -1; }
     if (n == 0) return 0;
@@ -331,9 +347,7 @@ namespace {
 int prefill_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
                    const int32_t* cu_q, const int64_t* kv_lens, int n, float scale, const PagedKv* paged, const NewRows* fresh = nullptr) {
     const int H = ctx->cfg.num_kv_heads, Hq = ctx->cfg.num_q_heads, D = ctx->cfg.head_dim;
-    // the wide kernel (four waves of 64 rows, software-pipelined) is opt-in: measured slower
-    const bool wide = ctx->prefill_wide && !paged && !fresh;
-    const PrefillQueues queues = make_prefill_queues(reqids, cu_q, kv_lens, n, Hq, H, ctx->num_cus, wide);
+    const PrefillQueues queues = make_prefill_queues(reqids, cu_q, kv_lens, n, Hq, H, ctx->num_cus);
     const int waves = queues.waves;
     const size_t per_xcd = static_cast<size_t>(queues.per_xcd);
     if (per_xcd == 0) return 0;
@@ -376,9 +390,9 @@ int prefill_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void*
     a.queue_heads = reinterpret_cast<int*>(d + off_ctr); a.num_cus = ctx->num_cus;
     if (fresh) { a.k_new = fresh->k_new; a.v_new = fresh->v_new; }
     LaunchEvents ev;
-    if (ctx->timing && !ctx->timers[1].next(&ev.start, &ev.stop)) return -1;
-    if (!(wide ? launch_prefill_wide(a, s, ev) : launch_prefill(a, s, ev))) return -1;
-    return 0;
+    if (ctx->timing && !ctx->timers[1].next(&ev.start, &ev.stop)) { (void)ctx->ring.release(s); return -1; }
+    const bool ok = launch_prefill(a, s, ev);
+    return ctx->ring.release(s) && ok ? 0 : -1;   // the slot (index arrays, work queues, queue counters) stays taken until the kernel ends
 }
 
 }  // namespace
@@ -387,6 +401,7 @@ extern "C" {
 
 int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
                        const int32_t* cu_q, const int64_t* kv_lens, int n, float scale) {
+    if (!check_scale(scale, "attn_prefill")) return -1;
     if (!check_ctx_layer(ctx, layer, "attn_prefill")) return -1;
     if (n < 0 || (n > 0 && (!q || !o || !reqids || !cu_q || !kv_lens))) { set_error("attn_prefill: null argument"); return -1; }
     if (n == 0) return 0;
@@ -402,6 +417,7 @@ int vattn_attn_prefill(vattn_ctx* ctx, int layer, void* stream, const void* q, v
 
 int vattn_attn_prefill_append(vattn_ctx* ctx, int layer, void* stream, const void* q, const void* k_new, const void* v_new, void* o,
                               const int32_t* reqids, const int32_t* cu_q, const int64_t* kv_lens, int n, float scale) {
+    if (!check_scale(scale, "attn_prefill_append")) return -1;
     if (!check_ctx_layer(ctx, layer, "attn_prefill_append")) return -1;
     if (n < 0 || (n > 0 && (!q || !k_new || !v_new || !o || !reqids || !cu_q || !kv_lens))) { set_error("attn_prefill_append: null argument"); return -1; }
     if (n == 0) return 0;
@@ -421,6 +437,7 @@ int vattn_attn_prefill_append(vattn_ctx* ctx, int layer, void* stream, const voi
 int vattn_attn_prefill_paged(vattn_ctx* ctx, void* stream, const void* q, void* o, const void* k_pool, const void* v_pool,
                              int64_t num_blocks, int block_tokens, const int32_t* block_table, int max_blocks_per_req,
                              const int32_t* cu_q, const int64_t* kv_lens, int n, float scale) {
+    if (!check_scale(scale, "attn_prefill_paged")) return -1;
     if (!ctx) { set_error("attn_prefill_paged: null context"); return -1; }
     if (n < 0 || (n > 0 && (!q || !o || !k_pool || !v_pool || !block_table || !cu_q || !kv_lens))) { set_error("attn_prefill_paged: null argument"); return -1; }
     if (n == 0) return 0;
@@ -458,12 +475,6 @@ int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* laun
 int vattn_set_decode_chunk(vattn_ctx* ctx, int tokens) {
     if (!ctx || tokens < 0 || tokens % 32 != 0) { set_error("set_decode_chunk: tokens must be a non-negative multiple of 32"); return -1; }
     ctx->decode_chunk = tokens;
-    return 0;
-}
-
-int vattn_set_prefill_wide(vattn_ctx* ctx, int enabled) {
-    if (!ctx) { set_error("set_prefill_wide: null context"); return -1; }
-    ctx->prefill_wide = enabled != 0;
     return 0;
 }
 

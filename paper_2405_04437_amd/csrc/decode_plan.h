@@ -7,7 +7,8 @@
 // size.  Workgroup s of a launch runs on XCD s % 8 and the XCDs do not draw the same bandwidth, so the
 // segment lengths repeat with period 8 and follow eight weights; the last period may be cut short by the
 // end of the sequence.  Segment s owns tiles [(s/8)*period + pre[s%8], (s/8)*period + pre[s%8 + 1]),
-// clipped to the sequence; a segment may be empty.
+// clipped to the sequence.  Inside the sequence no segment is empty (only the grid's padding segments
+// past num_segs are).
 #pragma once
 
 #include <algorithm>
@@ -53,6 +54,15 @@ inline DecodePlan make_decode_plan(const int64_t* kv_lens, int n, int chunk_toke
                 int best = 0;
                 for (int x = 1; x < 8; ++x) if (frac[x] > frac[best]) best = x;
                 ++len[best]; frac[best] = -1;
+            }
+            // No segment of a full period may be empty: the reduce kernel reads every partial slot between a
+            // request's first and last segment, and an empty segment writes none.  A weight small enough to
+            // round to zero tiles takes one from the longest segment instead (P >= 64, so that one stays long).
+            for (int x = 0; x < 8; ++x) {
+                if (len[x] > 0) continue;
+                int longest = 0;
+                for (int y = 1; y < 8; ++y) if (len[y] > len[longest]) longest = y;
+                --len[longest]; ++len[x];
             }
         }
     }

@@ -222,9 +222,15 @@ bool MetaRing::commit(size_t bytes, hipStream_t stream) {
     char* h = host_ + static_cast<size_t>(cur_) * slot_bytes_;
     char* d = dev_ + static_cast<size_t>(cur_) * slot_bytes_;
     if (!hip_ok(hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, stream), "hipMemcpyAsync (index upload)")) return false;
+    // Until release() records the slot's event the slot counts as busy up to this point of the stream.
     if (!hip_ok(hipEventRecord(ev_[cur_], stream), "hipEventRecord")) return false;
     pending_[cur_] = true;
     return true;
+}
+
+bool MetaRing::release(hipStream_t stream) {
+    if (cur_ < 0 || !pending_[cur_]) return true;
+    return hip_ok(hipEventRecord(ev_[cur_], stream), "hipEventRecord");
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -1,5 +1,5 @@
 // KV append: the new K and V rows of every request are copied to the end of its virtually
-// contiguous sub-tensor ("a single tensor copy" - Sec. 7.1 of the paper).  Pure data movement:
+// contiguous sub-tensor (Sec. 7.1 of the paper: with contiguous KV the append is one plain copy).  Pure data movement:
 // 16 bytes per lane, rows are H*D*P bytes and land at consecutive addresses (tok_stride = H*D*P; with
 // the all-layers-in-one-buffer layout consecutive tokens of a layer are N*H*D*P apart and each row is
 // still one contiguous piece), so both the reads and the writes are fully coalesced.

@@ -121,6 +121,12 @@ bool KvMemory::init(const vattn_config& c, const VmmOps& ops) {
         return false;
     }
 
+    // The per-reqId tables exist before the first driver call: if a reservation or a handle creation below
+    // fails, the destructor finds a consistent (empty) state and releases what was made so far.
+    held_.assign(static_cast<size_t>(B_), {});
+    active_.assign(static_cast<size_t>(B_), 0);
+    mapped_.assign(static_cast<size_t>(B_), 0);
+    committed_.assign(static_cast<size_t>(B_), 0);
     const size_t buf_bytes = static_cast<size_t>(B_) * static_cast<size_t>(S_);
     base_.assign(static_cast<size_t>(nbuf_), nullptr);
     for (size_t b = 0; b < base_.size(); ++b) {
@@ -134,10 +140,6 @@ bool KvMemory::init(const vattn_config& c, const VmmOps& ops) {
         if (!ops_.create(&h, static_cast<size_t>(G_), device_)) return false;
         free_handles_.push_back(h);
     }
-    held_.assign(static_cast<size_t>(B_), {});
-    active_.assign(static_cast<size_t>(B_), 0);
-    mapped_.assign(static_cast<size_t>(B_), 0);
-    committed_.assign(static_cast<size_t>(B_), 0);
     if (background_) {
         const VmmOps o = ops_;
         const int dev = device_;
@@ -151,7 +153,7 @@ KvMemory::~KvMemory() {
     sync();
     (void)ops_.bind_thread(device_);
     (void)ops_.device_sync();
-    for (int r = 0; r < B_; ++r) unmap_rows(r, 0);
+    for (int r = 0; r < static_cast<int>(mapped_.size()); ++r) unmap_rows(r, 0);
     for (auto h : free_handles_) (void)ops_.release(h);
     const size_t buf_bytes = static_cast<size_t>(B_) * static_cast<size_t>(S_);
     for (char* p : base_) if (p) (void)ops_.va_free(p, buf_bytes);
@@ -268,7 +270,13 @@ int KvMemory::step(const int64_t* seq_lens, int count) {
         set_error("step: physical pool exhausted (demand " + std::to_string(demand) + " page-groups, free " + std::to_string(free_now()) + ")");
         return -1;
     }
+    // What this call changes, so that a failing driver call can be rolled back: the mapped count of every reqId
+    // at entry (active ones grow, inactive ones may be reclaimed from).
+    const std::vector<int64_t> before = mapped_;
     if (demand > free_now()) {  // deferred policy: take pages back from inactive ids, lowest id first
+        // A request that was freed a moment ago may still be read by a kernel that is enqueued or running:
+        // nothing is unmapped before the device has drained (rare path - only when the pool is short).
+        (void)ops_.device_sync();
         for (int r = 0; r < B_ && free_now() < demand; ++r) {
             if (active_[r]) continue;
             while (mapped_[r] > 0 && free_now() < demand) unmap_rows(r, mapped_[r] - 1);
@@ -278,6 +286,19 @@ int KvMemory::step(const int64_t* seq_lens, int count) {
     for (int r = 0; r < B_; ++r) {
         if (!active_[r] || want[r] <= mapped_[r]) continue;
         if (!map_rows(r, mapped_[r], want[r], false)) { rc = -1; break; }
+    }
+    if (rc != 0) {
+        // A driver call failed (map_rows has already undone its own request).  All-or-nothing: the requests
+        // that grew earlier in this call shrink back, then the page-groups reclaimed from inactive ids are
+        // mapped again - if the driver refuses that too they stay in the pool, which an inactive id may not
+        // rely on anyway.  The error text of the first failure is kept.
+        const std::string first = last_error_string();
+        for (int r = 0; r < B_; ++r)
+            if (active_[r] && mapped_[r] > before[r]) unmap_rows(r, before[r]);
+        for (int r = 0; r < B_; ++r)
+            if (!active_[r] && mapped_[r] < before[r] && (before[r] - mapped_[r]) * per_row <= free_now())
+                (void)map_rows(r, mapped_[r], before[r], false);
+        set_error(first);
     }
     committed_ = mapped_;
     if (rc == 0 && background_) {

@@ -19,24 +19,22 @@ namespace vattn {
 struct PrefillItem { int32_t req; int32_t kvh; int32_t q_tile; int32_t reqid; int32_t q_begin; int32_t q_len; int32_t kv_len; int32_t pad; };
 
 struct PrefillQueues {
-    int waves;                        // default kernel: waves per workgroup (8 or 12)
-    int rows_per_item;                // BM: 32 * waves, or 256 for the wide kernel
+    int waves;                        // waves per workgroup (8 or 12)
+    int rows_per_item;                // BM: 32 * waves
     int per_xcd;                      // entries per queue, padding included
     std::vector<PrefillItem> items;   // 8 * per_xcd entries, queue x at [x * per_xcd, (x + 1) * per_xcd)
 };
 
-// Default kernel: twelve waves (384 rows per work item, three waves per SIMD) when that still leaves every
-// CU several work items, else eight waves (256 rows).  The wide kernel always takes 256 rows.
+// Twelve waves (384 rows per work item, three waves per SIMD) when that still leaves every CU several work
+// items, else eight waves (256 rows).
 // reqids may be null (paged comparison variant: the record then carries 0).
-inline PrefillQueues make_prefill_queues(const int32_t* reqids, const int32_t* cu_q, const int64_t* kv_lens, int n, int Hq, int H, int num_cus, bool wide) {
+inline PrefillQueues make_prefill_queues(const int32_t* reqids, const int32_t* cu_q, const int64_t* kv_lens, int n, int Hq, int H, int num_cus) {
     PrefillQueues out{};
     out.waves = 8;
-    if (!wide) {
-        int64_t items12 = 0;
-        for (int r = 0; r < n; ++r) items12 += (static_cast<int64_t>(cu_q[r + 1]) - cu_q[r] + 383) / 384 * Hq;
-        if (items12 >= 4 * static_cast<int64_t>(num_cus)) out.waves = 12;
-    }
-    const int BM = wide ? 256 : 32 * out.waves;
+    int64_t items12 = 0;
+    for (int r = 0; r < n; ++r) items12 += (static_cast<int64_t>(cu_q[r + 1]) - cu_q[r] + 383) / 384 * Hq;
+    if (items12 >= 4 * static_cast<int64_t>(num_cus)) out.waves = 12;
+    const int BM = 32 * out.waves;
     out.rows_per_item = BM;
     const int nsplit = H < 8 ? (8 + H - 1) / H : 1;
     struct Cost { PrefillItem it; int64_t cost; };

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../../include/vattn.h"
+#include "../../include/vattn_bench.h"
 #include "decode_plan.h"
 #include "prefill_plan.h"
 #include "kv_memory.h"
@@ -34,6 +35,10 @@ public:
     bool acquire(size_t bytes, char** host, char** dev);
     // Enqueues the upload of the first `bytes` bytes of the acquired slot on `stream`.
     bool commit(size_t bytes, hipStream_t stream);
+    // Call after the last kernel that reads the slot's device mirror has been enqueued on `stream`: moves the
+    // slot's event behind those kernels, so that the slot is only handed out again (eight acquisitions later,
+    // possibly for a call on another stream) once they have finished - not merely once the upload has.
+    bool release(hipStream_t stream);
 
 private:
     static constexpr int kSlots = 8;
@@ -118,7 +123,7 @@ struct PrefillArgs {
     int items_per_xcd; int n;
     int* queue_heads;                       // device: 8 counters, zero at launch: next slot of each XCD's queue (default kernel)
     int num_cus;
-    int waves;                              // default kernel: waves per workgroup (8 or 12); a work item is 32*waves rows
+    int waves;                              // waves per workgroup (8 or 12); a work item is 32*waves rows
     // Paged comparison variant only (default kernel): k_base / v_base are block pools [num_blocks, block_tokens,
     // H, D]; block_table[req * table_stride + j] names the block with tokens j*block_tokens .. of batch slot req.
     const int32_t* block_table; int table_stride; int block_tokens;
@@ -127,13 +132,11 @@ struct PrefillArgs {
     // kernel stores at positions kv_len - q_len .. kv_len - 1 and reads from here instead of from the cache (else null).
     const void* k_new; const void* v_new;
 };
-// Two kernels: the default with 32 query rows per wave and `waves` = 8 or 12 waves per work item, and a
-// wide one with 4 waves x 64 rows (software-pipelined); one workgroup per CU in all cases.
-// Measured on C3 / C5 for the default: 12 waves (three per SIMD) 1.18 / 1.22 PFLOP/s, 8 waves 1.13 / 1.19;
+// 32 query rows per wave and `waves` = 8 or 12 waves per work item; one workgroup per CU.
+// Measured on C3 / C5: 12 waves (three per SIMD) 1.18 / 1.22 PFLOP/s, 8 waves 1.13 / 1.19;
 // 4 waves with two workgroups per CU 1.07 / 1.12; 6 waves at three per SIMD in two workgroups 0.97 / 1.00.
 // Twelve waves need many work items: a 2048-token chunk (C4) runs 20 % slower with them than with eight.
 bool launch_prefill(const PrefillArgs& a, hipStream_t stream, LaunchEvents ev = {});
-bool launch_prefill_wide(const PrefillArgs& a, hipStream_t stream, LaunchEvents ev = {});
 
 }  // namespace vattn
 
@@ -146,6 +149,5 @@ struct vattn_ctx {
     int decode_chunk = 0;
     int decode_oversub = 1;  // segments per resident workgroup slot
     float decode_xcd_weight[8] = {1.f, 0.9f, 1.f, 0.9f, 1.f, 0.9f, 1.f, 0.9f};   // relative segment length per XCD
-    bool prefill_wide = false;
     int num_cus = 0;
 };

@@ -3,12 +3,14 @@
 // plain C++ compiler (optionally with a thread sanitizer) by tests/test_host_manager.py.
 //
 // Commands:  init N B L H D G pool flags lookahead eager threshold | a | f <reqid> | s <len>*B | q | quit
+//            fail <reserve|create|map|access> <k>   the k-th call of that operation from now on fails, once
 #include <cstdio>
 #include <iostream>
 #include <map>
 #include <mutex>
 #include <set>
 #include <sstream>
+#include <string>
 
 #include "../../paper_2405_04437_amd/csrc/kv_memory.h"
 
@@ -27,10 +29,19 @@ size_t g_G = 0;
 
 bool bad(const char* what) { ++g_violations; vattn::set_error(what); return false; }
 
+// Injected driver failures: countdown per operation (0 = none armed); the call that takes it to zero fails.
+enum { kReserve, kCreate, kMap, kAccess, kOps };
+long g_fail_in[kOps] = {};
+bool injected(int op, const char* what) {
+    if (g_fail_in[op] > 0 && --g_fail_in[op] == 0) { vattn::set_error(std::string("injected failure: ") + what); return true; }
+    return false;
+}
+
 bool f_bind(int) { return true; }
 bool f_gran(int, size_t* b) { *b = 4096; return true; }
 bool f_reserve(void** va, size_t bytes, size_t align) {
     std::lock_guard<std::mutex> lk(g_mu);
+    if (injected(kReserve, "reserve")) return false;
     g_next_va = (g_next_va + align - 1) / align * align;
     *va = reinterpret_cast<void*>(g_next_va);
     g_next_va += bytes;
@@ -39,6 +50,7 @@ bool f_reserve(void** va, size_t bytes, size_t align) {
 bool f_va_free(void*, size_t) { return true; }
 bool f_create(uint64_t* h, size_t bytes, int) {
     std::lock_guard<std::mutex> lk(g_mu);
+    if (injected(kCreate, "create")) return false;
     g_G = bytes;
     *h = g_next_handle++;
     g_alive.insert(*h);
@@ -52,6 +64,7 @@ bool f_release(uint64_t h) {
 bool f_map(void* va, size_t bytes, uint64_t h) {
     std::lock_guard<std::mutex> lk(g_mu);
     const uintptr_t a = reinterpret_cast<uintptr_t>(va);
+    if (injected(kMap, "map")) return false;
     if (bytes != g_G || a % g_G) return bad("map: wrong size or alignment");
     if (!g_alive.count(h)) return bad("map: unknown handle");
     if (g_in_use.count(h)) return bad("map: handle already mapped");
@@ -63,6 +76,7 @@ bool f_map(void* va, size_t bytes, uint64_t h) {
 bool f_access(void* va, size_t bytes, int) {
     std::lock_guard<std::mutex> lk(g_mu);
     const uintptr_t a = reinterpret_cast<uintptr_t>(va);
+    if (injected(kAccess, "access")) return false;
     for (uintptr_t x = a; x < a + bytes; x += g_G) {
         if (!g_mapped.count(x)) return bad("set_access over an unmapped range");
         g_access.insert(x);
@@ -120,6 +134,14 @@ int main() {
                         (long long)c.background_map_calls, (long long)mem->S(), g_violations, g_mapped.size());
             for (int r = 0; r < cfg.max_batch; ++r) std::printf(" %d:%lld:%lld", mem->is_active(r) ? 1 : 0, (long long)mem->mapped(r), (long long)mem->mapped_committed(r));
             std::printf("\n");
+        } else if (cmd == "fail") {
+            std::string op; long k = 0;
+            in >> op >> k;
+            const int which = op == "reserve" ? kReserve : op == "create" ? kCreate : op == "map" ? kMap : op == "access" ? kAccess : -1;
+            if (which >= 0) g_fail_in[which] = k;
+            std::printf("%d\n", which >= 0 ? 0 : -1);
+        } else if (cmd == "err") {
+            std::printf("%s\n", vattn::last_error_string().c_str());
         } else if (cmd == "quit") {
             break;
         }

@@ -140,36 +140,33 @@ def test_context_of_one_returns_v_bit_exactly():
             assert np.array_equal(p[r, h], inp.v[r][0, h // shape.group])
 
 
-def _run_prefill(shape, q_lens, kv_lens, seed, G=2 * MiB, wide=False):
+def _run_prefill(shape, q_lens, kv_lens, seed, G=2 * MiB):
     from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
 
     inp = W.draw_attention_inputs(shape, q_lens, kv_lens, seed)
     scale = W.softmax_scale(shape.head_dim)
     s = _session(shape, len(q_lens), max(kv_lens), G)
     reqids = s.load_contexts(inp.k, inp.v)
-    assert s.va.set_prefill_wide(wide) == 0
     got = tensor_to_f32(s.prefill(0, bits_to_tensor(inp.q), reqids, inp.cu_q, kv_lens, scale))
     s.close()
     want = OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale)
     return got, want
 
 
-@pytest.mark.parametrize("wide", [False, True])
 @pytest.mark.parametrize("Hq,H,D", [(8, 2, 64), (32, 8, 128), (14, 2, 128), (4, 4, 64), (3, 3, 128)])
-def test_prefill_shapes_ragged_lengths(Hq, H, D, wide):
+def test_prefill_shapes_ragged_lengths(Hq, H, D):
     shape = W.Shape("t", Hq, H, D, 1)
     q_lens = [1, 5, 64, 127, 128, 129, 300, 0, 513, 1100]
-    got, want = _run_prefill(shape, q_lens, list(q_lens[:7]) + [10, 513, 1100], seed=Hq + D, wide=wide)
-    check(got, want, f"prefill Hq={Hq} H={H} D={D} wide={wide}")
+    got, want = _run_prefill(shape, q_lens, list(q_lens[:7]) + [10, 513, 1100], seed=Hq + D)
+    check(got, want, f"prefill Hq={Hq} H={H} D={D}")
 
 
 def test_prefill_chunk_appended_to_existing_context():
     """A 300-token chunk appended at context 1000 attends to all 1300 tokens (config 4's shape of
     request, scaled down), together with fresh prompts and a decode-like q_len=1 row."""
     shape = W.YI_34B
-    for wide in (False, True):
-        got, want = _run_prefill(shape, [300, 200, 1, 77], [1300, 200, 555, 400], seed=12, wide=wide)
-        check(got, want, f"chunked prefill wide={wide}")
+    got, want = _run_prefill(shape, [300, 200, 1, 77], [1300, 200, 555, 400], seed=12)
+    check(got, want, "chunked prefill")
 
 
 def test_decode_equals_last_prefill_row_on_gpu():

@@ -61,18 +61,14 @@ def test_config3_llama3_8b_prefill_sampled_rows():
     kv = [_fill(sess, torch, gen, shape, r, L, keep=True) for r, L in zip(ids, wl.kv_lens)]
     cu = np.zeros(wl.n + 1, dtype=np.int64); cu[1:] = np.cumsum(wl.q_lens)
     q = torch.cat([_randn_bf16(torch, gen, (L, shape.num_q_heads, shape.head_dim)) for L in wl.q_lens])
-    outs = {}
-    for wide in (False, True):
-        assert sess.va.set_prefill_wide(wide) == 0
-        outs[wide] = sess.prefill(0, q, ids, cu, wl.kv_lens, scale)
+    out = sess.prefill(0, q, ids, cu, wl.kv_lens, scale)
     torch.cuda.synchronize()
     for r in range(wl.n):
         rows = W.sample_rows(wl.q_lens[r], 64, seed=wl.seed + r, boundaries=_boundaries(wl.q_lens[r], 0, shape))
         qb = tensor_to_bits(q[int(cu[r]):int(cu[r + 1])])
         want = OA.attention_request(qb, kv[r][0], kv[r][1], scale, rows=rows)
-        for wide in (False, True):
-            got = tensor_to_f32(outs[wide][int(cu[r]):int(cu[r + 1])][torch.from_numpy(rows.astype(np.int64)).cuda()])
-            check(got, want, f"C3 prompt {r} (len {wl.q_lens[r]}) wide={wide}")
+        got = tensor_to_f32(out[int(cu[r]):int(cu[r + 1])][torch.from_numpy(rows.astype(np.int64)).cuda()])
+        check(got, want, f"C3 prompt {r} (len {wl.q_lens[r]})")
     sess.close()
 
 
@@ -157,11 +153,9 @@ def test_config5_long_context_prefill_then_decode():
     # the oracle takes the request's own query rows: evaluate each sampled row as a one-row chunk whose
     # context ends at that row (the same causal definition, without materialising all of Q on the host)
     want = np.stack([OA.attention_request(qb_rows[j:j + 1], k_b[:r + 1], v_b[:r + 1], scale)[0] for j, r in enumerate(rows)])
-    for wide in (False, True):
-        assert sess.va.set_prefill_wide(wide) == 0
-        o = sess.prefill(0, q, [rid], [0, L], [L], scale)
-        got = tensor_to_f32(o[torch.from_numpy(rows.astype(np.int64)).cuda()])
-        check(got, want, f"C5 prefill wide={wide}")
+    o = sess.prefill(0, q, [rid], [0, L], [L], scale)
+    got = tensor_to_f32(o[torch.from_numpy(rows.astype(np.int64)).cuda()])
+    check(got, want, "C5 prefill")
     # decode steps: grow page by page through step(), split-K over the full context
     pages_before = sess.va.query(rid)[1]
     ks, vs = [k_b], [v_b]

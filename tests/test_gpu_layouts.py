@@ -131,10 +131,8 @@ def test_sub_tensor_beyond_4gib_is_addressed_correctly():
     q = torch.randn((ql, 32, 128), generator=gen, device="cuda").to(torch.bfloat16)
     rows = W.sample_rows(ql, 6, seed=3, boundaries=[128, ql - 129])
     want = OA.attention_request(tensor_to_bits(q), kb, vb, scale, rows=rows)
-    for wide in (False, True):
-        assert s.va.set_prefill_wide(wide) == 0
-        o = s.prefill(layer, q, [rid], [0, ql], [L], scale)
-        check(tensor_to_f32(o)[rows], want, f"prefill beyond 4 GiB wide={wide}")
+    o = s.prefill(layer, q, [rid], [0, ql], [L], scale)
+    check(tensor_to_f32(o)[rows], want, "prefill beyond 4 GiB")
     od = s.decode(layer, q[ql - 1:ql], [rid], [L], scale)
     check(tensor_to_f32(od), want[-1:], "decode beyond 4 GiB")   # sample_rows always includes the last row
     s.close()

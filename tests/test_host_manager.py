@@ -142,3 +142,55 @@ def test_pool_exhaustion_is_exercised(plain_exe):
     # the traces above must actually reach the failure branch of step(), or they pin less than they claim
     _, failures = _run_trace(plain_exe, 99, "deferred", True, True, steps=600)
     assert failures > 0
+
+
+# ---- injected driver failures (Sec. 5.3.3: step() "returns with a failure"; here: and changes nothing) -------------
+
+
+@pytest.mark.parametrize("op,k", [("reserve", 1), ("reserve", 4), ("create", 1), ("create", 4), ("create", 40)])
+def test_init_that_fails_partway_returns_minus_one_and_releases_everything(plain_exe, op, k):
+    h = Harness(plain_exe)
+    assert h.cmd(f"fail {op} {k}") == "0"
+    assert h.cmd("init 3 8 3000 2 64 8192 40 0 0 0 0") == "-1"     # 6 reservations, 40 handles
+    assert "injected failure" in h.cmd("err")
+    # the same process can still build a working manager afterwards
+    assert h.cmd("init 3 8 3000 2 64 8192 40 0 0 0 0") == "0"
+    assert h.cmd("a") == "0"
+    rc, out, err = h.close()
+    assert rc == 0 and "viol 0 live 0 alive 0" in out, (out, err[-2000:])
+
+
+@pytest.mark.parametrize("policy", ["sync", "deferred"])
+@pytest.mark.parametrize("op", ["map", "access"])
+def test_step_restores_its_entry_state_when_a_driver_call_fails(plain_exe, policy, op):
+    N, B, L, H, D, G = 2, 6, 4000, 2, 64, 8192          # 256 B per token: 32 tokens per page-group, 4 buffers
+    pool = 4 * 40
+    reached = 0
+    for k in (1, 2, 3, 5, 6, 9, 13):                       # first call, inside a row, across rows and across requests
+        h = Harness(plain_exe)
+        assert h.cmd(f"init {N} {B} {L} {H} {D} {G} {pool} {POLICY[policy]} 0 0 0") == "0"
+        ids = [int(h.cmd("a")) for _ in range(4)]
+        assert ids == [0, 1, 2, 3]
+        assert h.cmd("s 300 200 100 40 0 0") == "0"     # 10 + 7 + 4 + 2 rows
+        if policy == "deferred":                        # leave backed, inactive ids behind and make the pool short
+            assert h.cmd("f 1") == "0" and h.cmd("f 3") == "0"
+            assert h.cmd("s 800 0 300 0 0 0") == "0"    # 25 + 10 rows: 21 more than mapped, 17 free - reqId 1 gives 4 back
+            lens = "860 0 360 0 0 0"                    # 27 + 12 rows: 4 more, none free - reqIds 1 and 3 give them back
+        else:
+            lens = "500 300 200 100 0 0"                # 16 + 10 + 7 + 4 rows
+        before = h.cmd("q")
+        vals0, state0, committed0 = _parse(before)
+        assert h.cmd(f"fail {op} {k}") == "0"
+        rc = h.cmd("s " + lens)
+        vals1, state1, committed1 = _parse(h.cmd("q"))
+        if rc == "-1":                                  # the armed call was reached
+            reached += 1
+            assert "injected failure" in h.cmd("err")
+            assert (state1, committed1, vals1["free"], vals1["live"]) == (state0, committed0, vals0["free"], vals0["live"]), (k, before)
+            assert h.cmd("s " + lens) == "0"            # and the same request succeeds once the driver does
+        else:
+            assert rc == "0"
+        assert vals1["viol"] == 0
+        rc, out, err = h.close()
+        assert rc == 0 and "viol 0 live 0 alive 0" in out, (out, err[-2000:])
+    assert reached >= 4                                 # the injected failure is hit at several depths of the call

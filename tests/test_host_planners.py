@@ -28,9 +28,9 @@ def planner():
         v = [int(x) for x in p.stdout.readline().split()]
         return {"total": v[0], "num_segs": v[1], "max_segs": v[2], "period": v[3], "pre": v[4:13]}
 
-    def queues(Hq, H, cus, wide, q_lens, kv_lens):
+    def queues(Hq, H, cus, q_lens, kv_lens):
         flat = [v for pair in zip(q_lens, kv_lens) for v in pair]
-        p.stdin.write(" ".join(str(x) for x in ["Q", Hq, H, cus, int(wide), len(q_lens), *flat]) + "\n")
+        p.stdin.write(" ".join(str(x) for x in ["Q", Hq, H, cus, len(q_lens), *flat]) + "\n")
         p.stdin.flush()
         v = [int(x) for x in p.stdout.readline().split()]
         items = np.array(v[3:], dtype=np.int64).reshape(8, v[2], 7) if v[2] else np.zeros((8, 0, 7), dtype=np.int64)
@@ -64,7 +64,7 @@ def check_plan(plan, lens, grid_pad=16):
     at = 0
     for s in range(plan["num_segs"]):
         t0, t1 = seg_range(plan, s)
-        assert t0 == at and t1 >= t0
+        assert t0 == at and t1 > t0          # no empty segment inside the sequence: the reduce kernels read every slot
         at = t1
     assert at == plan["total"]
     for s in range(plan["num_segs"], plan["num_segs"] + grid_pad):
@@ -120,6 +120,20 @@ def test_segment_lengths_follow_the_weights(planner, weights):
     assert plan["num_segs"] <= 256 and plan["num_segs"] > 256 - 8    # one round of the resident workgroups
 
 
+def test_a_weight_that_rounds_to_zero_tiles_still_gets_a_tile(planner):
+    """One long request, weights at the ends of the accepted range: 0.25 / 28.25 of a 70-tile period is less than a
+    tile.  Every partial slot the reduce kernel reads for the request must belong to a non-empty segment."""
+    weights = [0.25] + [4] * 7
+    lens = [71680]                                     # 2240 tiles over 32 periods: 70 tiles per period
+    plan = planner(0, 256, 1, weights, lens)
+    check_plan(plan, lens)
+    assert min(np.diff(plan["pre"])) >= 1 and plan["period"] == 70
+    first, last = seg_of(plan, 0), seg_of(plan, plan["total"] - 1)
+    for s in range(first, last + 1):
+        t0, t1 = seg_range(plan, s)
+        assert t1 > t0
+
+
 def test_short_batches_fall_back_to_equal_segments(planner):
     plan = planner(0, 256, 1, [4, 0.25, 1, 1, 0.25, 4, 2, 0.5], [100, 200, 50])       # 13 tiles
     check_plan(plan, [100, 200, 50])
@@ -127,17 +141,16 @@ def test_short_batches_fall_back_to_equal_segments(planner):
 
 
 @pytest.mark.parametrize("Hq,H", [(32, 8), (56, 8), (32, 4), (8, 2), (3, 3), (7, 1), (64, 16)])
-@pytest.mark.parametrize("wide", [False, True])
-def test_prefill_queues_hold_every_work_item_once(planner, Hq, H, wide):
+def test_prefill_queues_hold_every_work_item_once(planner, Hq, H):
     rng = np.random.default_rng(Hq * 31 + H)
     cases = [([0], [5]), ([1], [1]), ([300, 200, 1, 77, 0, 513], [1300, 200, 555, 400, 10, 577]),
              (rng.integers(4096, 32768, endpoint=True, size=8).tolist(),) * 2, ([2048], [10240]), ([131072], [131072])]
     for q_lens, kv_lens in cases:
-        pq = planner.queues(Hq, H, 256, wide, q_lens, kv_lens)
+        pq = planner.queues(Hq, H, 256, q_lens, kv_lens)
         many = sum(-(-q // 384) for q in q_lens) * Hq >= 4 * 256
-        assert pq["waves"] == (12 if many and not wide else 8)
+        assert pq["waves"] == (12 if many else 8)
         BM = pq["rows"]
-        assert BM == (256 if wide else 32 * pq["waves"])
+        assert BM == 32 * pq["waves"]
         want = {(r, kvh, t) for r, q in enumerate(q_lens) for t in range(-(-q // BM)) for kvh in range(H)}
         seen = []
         for x in range(8):
@@ -156,13 +169,13 @@ def test_prefill_queues_hold_every_work_item_once(planner, Hq, H, wide):
 
 def test_prefill_queues_keep_a_kv_stream_on_one_xcd(planner):
     """All query tiles of one (request, KV head) - or of one tile class when there are fewer than 8 KV heads - share a queue."""
-    pq = planner.queues(32, 8, 256, False, [5000, 9000, 4097], [5000, 9000, 5097])
+    pq = planner.queues(32, 8, 256, [5000, 9000, 4097], [5000, 9000, 5097])
     home = {}
     for x in range(8):
         for r, kvh, t in pq["items"][x][:, :3]:
             if r >= 0:
                 assert home.setdefault((int(r), int(kvh)), x) == x
-    pq = planner.queues(32, 4, 256, False, [5000, 9000, 4097], [5000, 9000, 5097])       # 4 KV heads: two tile classes each
+    pq = planner.queues(32, 4, 256, [5000, 9000, 4097], [5000, 9000, 5097])       # 4 KV heads: two tile classes each
     home = {}
     for x in range(8):
         for r, kvh, t in pq["items"][x][:, :3]:

@@ -16,7 +16,7 @@
   7. internal fragmentation per page-group size and layout.
 
 Everything runs through the C ABI (paper_2405_04437_amd.binding); no result is checked here - parity lives in
-tests/.  Usage: python paper_2405_04437_amd/vmm_report.py [--quick]
+tests/.  Usage: python vmm_report.py [--quick]
 """
 from __future__ import annotations
 
@@ -27,7 +27,7 @@ import time
 
 import numpy as np
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 KiB, MiB = 1024, 1024 * 1024
 CALLS = ["hipMemAddressReserve", "hipMemCreate", "hipMemMap", "hipMemSetAccess (per page-group)",
@@ -478,7 +478,7 @@ def main() -> int:
 
     torch.cuda.set_stream(torch.cuda.Stream())
     print(f"# Memory-manager measurements on {torch.cuda.get_device_name(0)}\n")
-    print("Command: `python paper_2405_04437_amd/vmm_report.py" + (" --quick" if args.quick else "") + (f" --only {args.only}" if args.only else "") + "`\n")
+    print("Command: `python vmm_report.py" + (" --quick" if args.quick else "") + (f" --only {args.only}" if args.only else "") + "`\n")
     sections = {1: lambda: api_latency(P, args.quick), 2: lambda: page_size_effect(P, torch, W, args.quick),
                 3: lambda: latency_hiding(P, torch, W, args.quick), 4: lambda: prefill_admission(P, torch, W, args.quick),
                 5: lambda: paged_overhead(P, torch, W, args.quick), 6: lambda: slicing_effect(P, torch, W, args.quick),
