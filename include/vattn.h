@@ -190,6 +190,20 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q /*d
                       void* o /*device*/, const int32_t* reqids /*host*/, const int64_t* kv_lens /*host*/,
                       int n, float scale, void* workspace /*device*/, size_t workspace_bytes);
 
+/* vattn_attn_decode for callers that cannot allocate device memory or let a library do so: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result as
+ * vattn_attn_decode without the workspace: the split-K partials live in a device array of 32 MiB that the
+ * library owns (one per GPU, held until the process ends), and the call performs no allocation, no copy and
+ * no upload - the index arrays travel in the kernel arguments.  Limits, else -1 with a message: n <= 256,
+ * and (segments + n) * Hq * (D + 2) * 4 bytes of partials (segments <= CUs + 8) must fit the array - e.g.
+ * 256 requests at Hq = 56, D = 128.  Nothing in the array has to start at zero (every slot the reduce
+ * kernel reads is written by the split-K kernel of the same call).  All calls on one GPU share the array:
+ * calls that may overlap on the device (different streams, or another context on the same GPU) race; keep
+ * them on one stream.  Kernel timing (vattn_set_timing) does not cover this entry point. */
+int vattn_attn_decode_static(vattn_ctx* ctx, int layer, void* stream, const void* q /*device*/,
+                             void* o /*device*/, const int32_t* reqids /*host*/, const int64_t* kv_lens /*host*/,
+                             int n, float scale);
+
 /* Decode attention with the KV append fused in (Sec. 7.1 names kernels that write the new K/V rows
  * themselves): k_new, v_new [n, H, D] bf16 (device) are the K/V rows of each request's NEWEST token;
  * kv_lens[r] counts that token (it is position kv_lens[r]-1, which step() must already have mapped).

@@ -60,6 +60,7 @@ def _load() -> ctypes.CDLL:
     lib.vattn_decode_workspace_bytes.restype = ctypes.c_int64
     lib.vattn_attn_decode.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32p, i64p, ctypes.c_int, ctypes.c_float, vp,
                                       ctypes.c_size_t]
+    lib.vattn_attn_decode_static.argtypes = [vp, ctypes.c_int, vp, vp, vp, i32p, i64p, ctypes.c_int, ctypes.c_float]
     lib.vattn_attn_decode_append.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, i32p, i64p, ctypes.c_int, ctypes.c_float, vp,
                                              ctypes.c_size_t]
     lib.vattn_attn_prefill_append.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, vp, i32p, i32p, i64p, ctypes.c_int, ctypes.c_float]
@@ -82,7 +83,7 @@ def _load() -> ctypes.CDLL:
                  "vattn_set_timing", "vattn_kernel_time", "vattn_set_decode_chunk", "vattn_set_decode_tuning",
                  "vattn_step_counters", "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
                  "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights",
-                 "vattn_mfma_microbench", "vattn_stream_microbench"):
+                 "vattn_mfma_microbench", "vattn_stream_microbench", "vattn_attn_decode_static"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -95,7 +96,7 @@ EXPORTED = ["vattn_init", "vattn_destroy", "vattn_alloc_reqid", "vattn_free_reqi
             "vattn_set_decode_chunk", "vattn_set_decode_tuning", "vattn_step_counters",
             "vattn_sync", "vattn_vmm_microbench", "vattn_attn_decode_paged", "vattn_attn_decode_append", "vattn_attn_prefill_paged",
             "vattn_attn_prefill_append", "vattn_set_decode_xcd_weights",
-            "vattn_mfma_microbench", "vattn_stream_microbench", "vattn_last_error"]
+            "vattn_mfma_microbench", "vattn_stream_microbench", "vattn_attn_decode_static", "vattn_last_error"]
 
 
 def last_error() -> str:
@@ -216,6 +217,11 @@ class Vattn:
         k, kp = _i64(kv_lens)
         return lib.vattn_attn_decode(self._h, layer, stream, _ptr(q), _ptr(o), rp, kp, len(r), scale,
                                      _ptr(workspace), workspace_bytes)
+
+    def attn_decode_static(self, layer: int, stream: int, q, o, reqids, kv_lens, scale: float) -> int:
+        r, rp = _i32(reqids)
+        k, kp = _i64(kv_lens)
+        return lib.vattn_attn_decode_static(self._h, layer, stream, _ptr(q), _ptr(o), rp, kp, len(r), scale)
 
     def attn_decode_append(self, layer: int, stream: int, q, k_new, v_new, o, reqids, kv_lens, scale: float, workspace,
                            workspace_bytes: int) -> int:

@@ -212,10 +212,13 @@ struct NewRows { const void* k_new; const void* v_new; };
 // Shared by vattn_attn_decode and vattn_attn_decode_paged: split-K plan, index upload, the two launches.
 int decode_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
                   const int64_t* kv_lens, int n, float scale, void* workspace, size_t workspace_bytes, const PagedKv* paged,
-                  const NewRows* fresh, const char* fn) {
+                  const NewRows* fresh, const char* fn, bool no_alloc = false) {
     const DecodePlan plan = plan_decode(ctx, kv_lens, n);
     if (plan.total_tiles > INT32_MAX) { set_error(std::string(fn) + ": batch too large"); return -1; }
     const bool inl = n <= kInlineMaxReq && !paged;
+    // The allocation-free entry point must stay clear of the staging ring (which grows with hipMalloc) and of
+    // the timers (which create events): its index arrays travel in the kernel arguments only.
+    if (no_alloc && !inl) { set_error(std::string(fn) + ": at most " + std::to_string(kInlineMaxReq) + " requests per call"); return -1; }
     InlineMeta im;
     const size_t off_kv = sizeof(int32_t) * n, off_cu = off_kv * 2;
     const size_t off_tab = align_up(off_cu + sizeof(int32_t) * (n + 1), 16);
@@ -272,7 +275,7 @@ int decode_common(vattn_ctx* ctx, int layer, void* stream, const void* q, void* 
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + part_o_bytes);
     const InlineMeta* imp = inl ? &im : nullptr;
     LaunchEvents ev_split, ev_reduce;
-    if (ctx->timing && (!ctx->timers[0].next(&ev_split.start, &ev_split.stop) || !ctx->timers[2].next(&ev_reduce.start, &ev_reduce.stop))) {
+    if (ctx->timing && !no_alloc && (!ctx->timers[0].next(&ev_split.start, &ev_split.stop) || !ctx->timers[2].next(&ev_reduce.start, &ev_reduce.stop))) {
         if (!inl) (void)ctx->ring.release(s);
         return -1;
     }
@@ -296,6 +299,28 @@ int vattn_attn_decode(vattn_ctx* ctx, int layer, void* stream, const void* q, vo
         if (!check_request(ctx, reqids[r], kv_lens[r], "attn_decode")) return -1;
     }
     return decode_common(ctx, layer, stream, q, o, reqids, kv_lens, n, scale, workspace, workspace_bytes, nullptr, nullptr, "attn_decode");
+}
+
+int vattn_attn_decode_static(vattn_ctx* ctx, int layer, void* stream, const void* q, void* o, const int32_t* reqids,
+                             const int64_t* kv_lens, int n, float scale) {
+    if (!check_scale(scale, "attn_decode_static")) return -1;
+    if (!check_ctx_layer(ctx, layer, "attn_decode_static")) return -1;
+    if (n < 0 || (n > 0 && (!q || !o || !reqids || !kv_lens))) { set_error("attn_decode_static: null argument"); return -1; }
+    if (n == 0) return 0;
+    for (int r = 0; r < n; ++r) {
+        if (kv_lens[r] < 1) { set_error("attn_decode_static: context length must be >= 1"); return -1; }
+        if (!check_request(ctx, reqids[r], kv_lens[r], "attn_decode_static")) return -1;
+    }
+    void* scratch_ptr = nullptr;
+    size_t scratch_bytes = 0;
+    if (!decode_static_scratch(ctx->cfg.device, &scratch_ptr, &scratch_bytes)) return -1;
+    const size_t need = decode_workspace_need(ctx, plan_decode(ctx, kv_lens, n), n);
+    if (need > scratch_bytes) {
+        set_error("attn_decode_static: this batch needs " + std::to_string(need) + " bytes of split-K partials, the library-owned array holds " +
+                  std::to_string(scratch_bytes) + "; use vattn_attn_decode with a caller-owned workspace");
+        return -1;
+    }
+    return decode_common(ctx, layer, stream, q, o, reqids, kv_lens, n, scale, scratch_ptr, scratch_bytes, nullptr, nullptr, "attn_decode_static", true);
 }
 
 int vattn_attn_decode_append(vattn_ctx* ctx, int layer, void* stream, const void* q, const void* k_new, const void* v_new, void* o,

@@ -403,6 +403,30 @@ __global__ __launch_bounds__(kReduceFewPairs * 64) void decode_reduce_few_kernel
 
 static const InlineMeta kNoInline{};
 
+// Split-K partials for callers that cannot allocate (vattn_attn_decode_static): a device array the library
+// itself owns, one copy per GPU, held until the process ends.  In host code the array's name is only a
+// stand-in; its device address is asked of the runtime once per device and kept.
+static __device__ __align__(256) unsigned char scratch[kDecodeScratchBytes];
+
+bool decode_static_scratch(int device, void** ptr, size_t* bytes) {
+    constexpr int kMaxDevices = 64;
+    static void* addr[kMaxDevices] = {};
+    if (device < 0 || device >= kMaxDevices) { set_error("attn_decode_static: device ordinal out of range"); return false; }
+    if (!addr[device]) {
+        int current = -1;
+        if (!hip_ok(hipGetDevice(&current), "hipGetDevice")) return false;
+        if (current != device && !hip_ok(hipSetDevice(device), "hipSetDevice")) return false;
+        void* p = nullptr;
+        const bool ok = hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress (decode scratch)");
+        if (current != device && current >= 0) (void)hipSetDevice(current);
+        if (!ok || !p) { if (ok) set_error("attn_decode_static: the runtime returned no address for the scratch array"); return false; }
+        addr[device] = p;
+    }
+    *ptr = addr[device];
+    *bytes = kDecodeScratchBytes;
+    return true;
+}
+
 static int waves_per_workgroup(int Hq, int H) {
     const int units = H * ((Hq / H + 15) / 16);
     return units < kMaxWaves ? units : kMaxWaves;

@@ -109,6 +109,9 @@ struct DecodeArgs {
     // Fused append only: newest K/V rows [n, H, D] of the batch, to be stored at position kv_len - 1 (else null).
     const void* k_new; const void* v_new;
 };
+// Device address and size of the library-owned partials array of `device` (vattn_attn_decode_static).
+constexpr size_t kDecodeScratchBytes = size_t{32} << 20;
+bool decode_static_scratch(int device, void** ptr, size_t* bytes);
 int decode_resident_workgroups(int Hq, int H, int D, int num_cus);  // workgroups one launch keeps resident
 bool launch_decode_splitk(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});   // paged if a.block_table
 bool launch_decode_reduce(const DecodeArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});
