@@ -247,12 +247,12 @@ int vattn_attn_prefill_paged(vattn_ctx* ctx, void* stream, const void* q /*devic
 
 /* ---- measurement helpers --------------------------------------------------------------------- */
 
-/* When enabled, every launch of the split-K decode kernel, the reduce kernel and the prefill kernel
- * carries a pair of HIP events that the launch stream records when the kernel starts and when it
+/* When enabled, every launch of the split-K decode kernel, the reduce kernel, the prefill kernel and the
+ * KV-append kernel carries a pair of HIP events that the launch stream records when the kernel starts and when it
  * ends (hipExtLaunchKernelGGL), so their distance is the kernel's execution time without launch
  * gaps; vattn_kernel_time() then synchronises those events and returns the accumulated kernel time
  * in milliseconds and the number of launches since the last call, per kernel (which: 0 = decode
- * split-K, 1 = prefill, 2 = decode reduce), and resets them. */
+ * split-K, 1 = prefill, 2 = decode reduce, 3 = KV append), and resets them. */
 int vattn_set_timing(vattn_ctx* ctx, int enabled);
 int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* launches);
 

@@ -160,6 +160,8 @@ int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new, 
         if (kv_len_before[r] < 0 || !check_request(ctx, reqids[r], kv_len_before[r] + ql, "append_kv")) return -1;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
+    LaunchEvents ev;
+    if (ctx->timing && !ctx->timers[3].next(&ev.start, &ev.stop)) return -1;
     AppendArgs a{};
     a.k_new = k_new; a.v_new = v_new;
     a.k_base = ctx->mem.buffer_base(layer, 0); a.v_base = ctx->mem.buffer_base(layer, 1);
@@ -170,7 +172,7 @@ int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new, 
         for (int r = 0; r < n; ++r) { im.v[r] = reqids[r]; im.v[n + r] = static_cast<int32_t>(kv_len_before[r]); }
         for (int r = 0; r <= n; ++r) im.v[2 * n + r] = cu_q[r];
         a.inline_meta = 1;
-        return launch_append_kv(a, &im, s) ? 0 : -1;
+        return launch_append_kv(a, &im, s, ev) ? 0 : -1;
     }
     const size_t off_kv = sizeof(int32_t) * n, off_cu = 2 * off_kv;
     const size_t bytes = off_cu + sizeof(int32_t) * (n + 1);
@@ -183,7 +185,7 @@ int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new, 
     a.reqids = reinterpret_cast<const int32_t*>(d);
     a.kv_before = reinterpret_cast<const int32_t*>(d + off_kv);
     a.cu_q = reinterpret_cast<const int32_t*>(d + off_cu);
-    const bool ok = launch_append_kv(a, nullptr, s);
+    const bool ok = launch_append_kv(a, nullptr, s, ev);
     return ctx->ring.release(s) && ok ? 0 : -1;
 }
 
@@ -493,7 +495,7 @@ int vattn_set_timing(vattn_ctx* ctx, int enabled) {
 }
 
 int vattn_kernel_time(vattn_ctx* ctx, int which, double* total_ms, int64_t* launches) {
-    if (!ctx || which < 0 || which > 2) { set_error("kernel_time: invalid argument"); return -1; }
+    if (!ctx || which < 0 || which > 3) { set_error("kernel_time: invalid argument"); return -1; }
     return ctx->timers[which].collect(total_ms, launches) ? 0 : -1;
 }
 

@@ -3,6 +3,8 @@
 // 16 bytes per lane, rows are H*D*P bytes and land at consecutive addresses (tok_stride = H*D*P; with
 // the all-layers-in-one-buffer layout consecutive tokens of a layer are N*H*D*P apart and each row is
 // still one contiguous piece), so both the reads and the writes are fully coalesced.
+#include <hip/hip_ext.h>
+
 #include "vattn_internal.h"
 
 namespace vattn {
@@ -39,15 +41,15 @@ __global__ __launch_bounds__(256) void append_kv_kernel(AppendArgs a, InlineMeta
 
 }  // namespace
 
-bool launch_append_kv(const AppendArgs& a, const InlineMeta* im, hipStream_t stream) {
+bool launch_append_kv(const AppendArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev) {
     if (a.total_rows == 0) return true;
     const int64_t total = static_cast<int64_t>(a.total_rows) * (a.row_bytes / 16);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 8192) blocks = 8192;
     dim3 grid(static_cast<unsigned>(blocks), 2);
     static const InlineMeta kNoInline{};
-    if (a.inline_meta && im) hipLaunchKernelGGL(append_kv_kernel<true>, grid, dim3(256), 0, stream, a, *im);
-    else hipLaunchKernelGGL(append_kv_kernel<false>, grid, dim3(256), 0, stream, a, kNoInline);
+    if (a.inline_meta && im) hipExtLaunchKernelGGL(append_kv_kernel<true>, grid, dim3(256), 0, stream, ev.start, ev.stop, 0, a, *im);
+    else hipExtLaunchKernelGGL(append_kv_kernel<false>, grid, dim3(256), 0, stream, ev.start, ev.stop, 0, a, kNoInline);
     return hip_ok(hipGetLastError(), "append_kv launch");
 }
 

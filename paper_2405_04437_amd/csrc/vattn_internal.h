@@ -82,7 +82,7 @@ struct AppendArgs {
     int n; int total_rows;
     int inline_meta;                        // 1: arrays are in InlineMeta as [reqids | kv_before | cu_q]
 };
-bool launch_append_kv(const AppendArgs& a, const InlineMeta* im, hipStream_t stream);
+bool launch_append_kv(const AppendArgs& a, const InlineMeta* im, hipStream_t stream, LaunchEvents ev = {});
 
 struct DecodeArgs {
     const void* q; void* o;                 // [n, Hq, D] bf16
@@ -147,7 +147,7 @@ struct vattn_ctx {
     vattn_config cfg{};
     vattn::KvMemory mem;
     vattn::MetaRing ring;
-    vattn::KernelTimer timers[3];
+    vattn::KernelTimer timers[4];   // split-K decode, prefill, decode reduce, KV append
     bool timing = false;
     int decode_chunk = 0;
     int decode_oversub = 1;  // segments per resident workgroup slot
