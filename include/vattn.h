@@ -92,9 +92,10 @@ typedef struct {
  * up to the page-group size (Sec. 5.1.3) - with TENSOR_SLICING, 2 buffers and S = L*N*H*D*P - and
  * creates the physical page-group pool WITHOUT mapping any of it.  *out receives the context.
  * Fails if the device lacks virtual-memory support, the configuration is invalid, the pool cannot
- * be created, or it holds more page-groups than the library allows: the smaller of 32768 and what
- * the process can keep mapped (each mapped page-group is one memory mapping of the process; Linux
- * caps them at vm.max_map_count).  Larger caches need larger page-groups. */
+ * be created, or it holds more than 32768 page-groups (larger caches need larger page-groups).
+ * Every (buffer, page-group) address that is ever mapped stays a memory mapping of the process until
+ * vattn_destroy(), also after it is unmapped, and Linux caps their number (vm.max_map_count): the
+ * library counts them, and step() returns -1 - changing nothing - before that cap would be reached. */
 int vattn_init(const vattn_config* cfg /*host*/, vattn_ctx** out /*host*/);
 
 /* Unmaps and releases everything, frees the reservations and the context.  The caller must have

@@ -63,14 +63,19 @@ bool vmm_set_access(void* va, size_t bytes, int device) {
 }
 bool vmm_unmap(void* va, size_t bytes) { return hip_ok(hipMemUnmap(va, bytes), "hipMemUnmap"); }
 
-// How many page-group handles one pool may hold.  Two bounds, the smaller wins:
-//  * every mapped page-group is a separate memory mapping of the process, and Linux caps those per
-//    process (vm.max_map_count, 65530 by default); room is left for the rest of the process;
-//  * pools of 65 536 handles and more were seen to crash the process inside the runtime on MI355X
-//    (with 4 KiB and with 64 KiB handles, during creation or mapping), while 27 648 handles worked;
-//    until that is understood the library refuses more than 32 768.
-// Larger caches need larger page-groups: 32 768 x 2 MiB = 64 GiB, x 16 MiB = 512 GiB.
-int64_t vmm_mapping_limit() {
+// How many page-group handles one pool may hold: pools of 65 536 handles and more were seen to crash the process
+// inside the runtime on MI355X (with 4 KiB and with 64 KiB handles, during creation or mapping), while 27 648
+// handles worked.  Measured since: hipMemCreate adds no memory mapping and no file descriptor to the process,
+// and the machine measured allows 1 048 576 mappings - so neither the cap on mappings (65 530 by default, which
+// is what the threshold looked like) nor the descriptor limit explains it.  The cause is still unknown, the
+// case was not run again, and the library keeps refusing more than 32 768.  Larger caches need
+// larger page-groups: 32 768 x 2 MiB = 64 GiB, x 16 MiB = 512 GiB.
+int64_t vmm_mapping_limit() { return 32768; }
+// Measured on MI355X / ROCm 7.2: hipMemMap adds 1.02-1.07 memory mappings of the process per page-group,
+// hipMemCreate and hipMemSetAccess none, and hipMemUnmap / hipMemRelease remove none - they only go away with
+// hipMemAddressFree.  So what counts against vm.max_map_count is every (buffer, page-group) address that was
+// EVER mapped; the budget leaves room for the rest of the process and for the 7 % on top.
+int64_t vmm_mapping_budget() {
     long v = 65530;
     if (FILE* f = std::fopen("/proc/sys/vm/max_map_count", "r")) {
         long x = 0;
@@ -78,8 +83,8 @@ int64_t vmm_mapping_limit() {
         std::fclose(f);
     }
     const long headroom = 16384;
-    const long by_mappings = v > 2 * headroom ? v - headroom : v / 2;
-    return by_mappings < 32768 ? by_mappings : 32768;
+    const long usable = v > 2 * headroom ? v - headroom : v / 2;
+    return static_cast<int64_t>(usable / 1.1);
 }
 int64_t no_mapping_limit() { return 0; }
 
@@ -97,13 +102,13 @@ bool static_unmap(void*, size_t) { return true; }
 
 const VmmOps& hip_vmm_ops() {
     static const VmmOps ops{op_bind, vmm_granularity, vmm_reserve, vmm_va_free, vmm_create, vmm_release,
-                            vmm_map, vmm_set_access, vmm_unmap, op_device_sync, vmm_mapping_limit};
+                            vmm_map, vmm_set_access, vmm_unmap, op_device_sync, vmm_mapping_limit, vmm_mapping_budget};
     return ops;
 }
 
 const VmmOps& hip_static_ops() {
     static const VmmOps ops{op_bind, static_granularity, static_reserve, static_va_free, static_create, static_release,
-                            static_map, static_set_access, static_unmap, op_device_sync, no_mapping_limit};
+                            static_map, static_set_access, static_unmap, op_device_sync, no_mapping_limit, no_mapping_limit};
     return ops;
 }
 

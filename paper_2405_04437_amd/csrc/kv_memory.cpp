@@ -8,6 +8,7 @@
 // prepares the next reqId and reclaims deferred pages while the caller runs the current iteration.
 #include "kv_memory.h"
 
+#include <algorithm>
 #include <chrono>
 
 namespace vattn {
@@ -116,14 +117,16 @@ bool KvMemory::init(const vattn_config& c, const VmmOps& ops) {
     const int64_t limit = ops_.mapping_limit ? ops_.mapping_limit() : 0;
     if (limit > 0 && pool_total_ > limit) {
         set_error("init: the pool has " + std::to_string(pool_total_) + " page-groups, but the limit is " +
-                  std::to_string(limit) + " (every mapped page-group is one memory mapping of the process, the operating "
-                  "system caps their number, and very large handle counts are not safe on this platform); use larger page-groups");
+                  std::to_string(limit) + " (very large handle counts are not safe on this platform); use larger page-groups");
         return false;
     }
 
     // The per-reqId tables exist before the first driver call: if a reservation or a handle creation below
     // fails, the destructor finds a consistent (empty) state and releases what was made so far.
     held_.assign(static_cast<size_t>(B_), {});
+    high_water_.assign(static_cast<size_t>(B_), 0);
+    touched_ = 0;
+    budget_ = ops_.mapping_budget ? ops_.mapping_budget() : 0;
     active_.assign(static_cast<size_t>(B_), 0);
     mapped_.assign(static_cast<size_t>(B_), 0);
     committed_.assign(static_cast<size_t>(B_), 0);
@@ -198,7 +201,14 @@ bool KvMemory::map_rows(int r, int64_t from, int64_t to, bool background) {
     const size_t nb = base_.size();
     auto& held = held_[r];
     const double t0 = now_us();
+    if (budget_ > 0 && to > high_water_[r] && touched_ + (to - std::max(high_water_[r], from)) * static_cast<int64_t>(nb) > budget_) {
+        set_error("mapping " + std::to_string(to - from) + " more page-group rows of reqId " + std::to_string(r) + " would exceed the " +
+                  std::to_string(budget_) + " distinct address slots this process may map (the system's cap on memory mappings; "
+                  "a slot stays a mapping after it is unmapped): use larger page-groups or a smaller B*L");
+        return false;
+    }
     for (int64_t k = from; k < to; ++k) {
+        if (k + 1 > high_water_[r]) { high_water_[r] = k + 1; touched_ += static_cast<int64_t>(nb); }
         for (size_t b = 0; b < nb; ++b) {
             const uint64_t h = free_handles_.back();
             char* va = base_[b] + static_cast<int64_t>(r) * S_ + k * G_;
@@ -266,6 +276,17 @@ int KvMemory::step(const int64_t* seq_lens, int count) {
     }
     const int64_t per_row = nbuf_;
     const int64_t demand = demand_rows * per_row;
+    if (budget_ > 0) {   // rows that were never mapped before take new address slots
+        int64_t fresh = 0;
+        for (int r = 0; r < B_; ++r)
+            if (active_[r] && want[r] > high_water_[r]) fresh += want[r] - std::max(high_water_[r], mapped_[r]);
+        if (touched_ + fresh * per_row > budget_) {
+            set_error("step: " + std::to_string(fresh * per_row) + " page-groups at addresses never mapped before would exceed the " +
+                      std::to_string(budget_) + " distinct address slots this process may map (the system's cap on memory mappings; "
+                      "a slot stays a mapping after it is unmapped): use larger page-groups or a smaller B*L");
+            return -1;
+        }
+    }
     if (demand > free_now() + reclaimable_rows * per_row) {
         set_error("step: physical pool exhausted (demand " + std::to_string(demand) + " page-groups, free " + std::to_string(free_now()) + ")");
         return -1;

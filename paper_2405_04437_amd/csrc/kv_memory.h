@@ -34,7 +34,11 @@ struct VmmOps {
     bool (*set_access)(void* va, size_t bytes, int device);        // read/write for the device
     bool (*unmap)(void* va, size_t bytes);
     bool (*device_sync)();                                         // wait for all work queued on the device
-    int64_t (*mapping_limit)();                                    // page-groups one process can keep mapped (0 = no limit)
+    int64_t (*mapping_limit)();                                    // most page-group handles one pool may hold (0 = no limit)
+    // How many DISTINCT (buffer, page-group) address slots a context may map over its whole life (0 = no limit):
+    // on Linux every slot that was ever mapped stays a separate memory mapping of the process until the
+    // reservation is freed - unmapping does not give it back - and the system caps their number.
+    int64_t (*mapping_budget)();
 };
 
 // One helper thread that runs one task at a time.  submit() and wait() are called from the thread
@@ -119,6 +123,8 @@ private:
     std::vector<std::vector<uint64_t>> held_;          // per reqId: rows x buffers handles
     std::vector<uint8_t> active_;
     std::vector<int64_t> mapped_;                      // owned by whichever thread currently runs (caller or pass)
+    std::vector<int64_t> high_water_;                  // per reqId: most rows ever mapped (each row touched nbuf_ address slots)
+    int64_t touched_ = 0, budget_ = 0;                 // address slots mapped at least once, and their cap (0 = none)
     std::vector<int64_t> committed_;                   // copy of mapped_ taken at sync(), read by launch validation
     Counters c_;
     Worker worker_;

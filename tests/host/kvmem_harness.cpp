@@ -4,6 +4,7 @@
 //
 // Commands:  init N B L H D G pool flags lookahead eager threshold | a | f <reqid> | s <len>*B | q | quit
 //            fail <reserve|create|map|access> <k>   the k-th call of that operation from now on fails, once
+//            budget <n>   the next init gets a cap of n distinct (buffer, page-group) address slots | err
 #include <cstdio>
 #include <iostream>
 #include <map>
@@ -94,11 +95,13 @@ bool f_unmap(void* va, size_t bytes) {
     return true;
 }
 bool f_sync() { return true; }
+long g_budget = 0;   // distinct address slots the next context may map over its life (0 = unlimited)
+int64_t f_budget() { return g_budget; }
 
 }  // namespace
 
 int main() {
-    const vattn::VmmOps ops{f_bind, f_gran, f_reserve, f_va_free, f_create, f_release, f_map, f_access, f_unmap, f_sync, nullptr};
+    const vattn::VmmOps ops{f_bind, f_gran, f_reserve, f_va_free, f_create, f_release, f_map, f_access, f_unmap, f_sync, nullptr, f_budget};
     vattn::KvMemory* mem = nullptr;
     vattn_config cfg{};
     std::string line;
@@ -140,6 +143,9 @@ int main() {
             const int which = op == "reserve" ? kReserve : op == "create" ? kCreate : op == "map" ? kMap : op == "access" ? kAccess : -1;
             if (which >= 0) g_fail_in[which] = k;
             std::printf("%d\n", which >= 0 ? 0 : -1);
+        } else if (cmd == "budget") {
+            in >> g_budget;
+            std::printf("0\n");
         } else if (cmd == "err") {
             std::printf("%s\n", vattn::last_error_string().c_str());
         } else if (cmd == "quit") {

@@ -194,3 +194,28 @@ def test_step_restores_its_entry_state_when_a_driver_call_fails(plain_exe, polic
         rc, out, err = h.close()
         assert rc == 0 and "viol 0 live 0 alive 0" in out, (out, err[-2000:])
     assert reached >= 4                                 # the injected failure is hit at several depths of the call
+
+
+def test_distinct_address_slots_are_capped_by_the_mapping_budget(plain_exe):
+    """Every (buffer, page-group) address that was ever mapped stays a memory mapping of the process until the
+    reservation is freed, and the system caps their number: the manager counts them and step() refuses - changing
+    nothing - what would go beyond the budget, while re-mapping addresses used before stays free of charge."""
+    N, B, L, H, D, G = 2, 4, 4000, 2, 64, 8192          # 32 tokens per page-group, 4 buffers
+    h = Harness(plain_exe)
+    assert h.cmd("budget 48") == "0"                     # 12 rows of 4 slots
+    assert h.cmd(f"init {N} {B} {L} {H} {D} {G} 400 1 0 0 0") == "0"
+    assert h.cmd("a") == "0" and h.cmd("a") == "1"
+    assert h.cmd("s 160 96 0 0") == "0"                  # 5 + 3 rows: 32 slots
+    before = h.cmd("q")
+    assert h.cmd("s 160 256 0 0") == "-1"                # reqId 1 to 8 rows: 5 new rows, 52 slots > 48
+    assert "distinct address slots" in h.cmd("err")
+    assert h.cmd("q") == before
+    assert h.cmd("s 160 224 0 0") == "0"                 # to 7 rows: exactly 48
+    # addresses that were mapped before can be unmapped and mapped again at will
+    assert h.cmd("f 1") == "0" and h.cmd("a") == "1"     # deferred: the pages stay; the id comes back
+    assert h.cmd("s 160 224 0 0") == "0"
+    assert h.cmd("a") == "2"
+    assert h.cmd("s 160 224 32 0") == "-1"               # a row at a fresh address: over the budget
+    assert h.cmd("s 160 224 0 0") == "0"
+    rc, out, err = h.close()
+    assert rc == 0 and "viol 0 live 0 alive 0" in out, (out, err[-2000:])
