@@ -134,9 +134,13 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, wh
     va, stream = sess.va, sess.stream
     torch_stream = torch.cuda.current_stream()
 
+    every = {"bytes": 0, "launches": 0}     # over every decode launch of this run, warm-up included (for counter runs)
+
     def one_step(i):
         seq[ids] = lens + 1
         _ok(va.step(seq))
+        every["bytes"] += (int(lens.sum() + n) * per_tok + qo_bytes) * (layers if whole_model else 1)
+        every["launches"] += layers if whole_model else 1
         if whole_model:                   # every layer: the new K/V row rides in that layer's decode kernel
             for layer in range(layers):
                 _ok(va.attn_decode_append(layer, stream, q, knew, vnew, o, ids, lens + 1, scale, ws, ws.numel()))
@@ -193,6 +197,7 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, wh
         "bytes_per_step": bytes_per_step,
         "kbytes_per_launch": kbytes_per_launch,
         "tokens_in_batch": int(lens.sum()),
+        "bytes_per_launch_over_all_launches": every["bytes"] / max(every["launches"], 1), "all_launches": every["launches"],
         "layers": layers, "decode_launches_per_step": launches_per_step,
         "map_calls_in_timed_region": map1[0] - map0[0],
         "map_us_in_timed_region": map1[2] - map0[2],
@@ -290,6 +295,7 @@ def run_mixed(args, torch, W, wl, steps, warmup):
     chunk_kv = np.array([chunk_ctx], dtype=np.int64)
     retired = []                                   # reqIds that left the batch in the previous window
     stat = {"arrival_map_demand": 0, "host_window_us": 0.0, "decode_bytes": 0}
+    every = {"bytes": 0, "launches": 0}           # over every decode launch of this run (for counter runs)
 
     def one_step(i, launch=True):
         t_host = time.perf_counter()
@@ -327,6 +333,7 @@ def run_mixed(args, torch, W, wl, steps, warmup):
         _ok(va.attn_decode_append(0, stream, q, knew, vnew, o, ids, lens + 1, scale, ws, ws.numel()))
         lens[:] += 1
         stat["decode_bytes"] += _decode_bytes(shape, lens)
+        every["bytes"] += _decode_bytes(shape, lens); every["launches"] += 1
         return rows_new
 
     def counters():
@@ -394,6 +401,8 @@ def run_mixed(args, torch, W, wl, steps, warmup):
                       "arrivals_kv_write_per_step": app_ms_step},
         "decode_gbs_kernel": dbytes / (dec_ms * 1e6), "decode_frac_of_hbm_peak": dbytes / (dec_ms * 1e6) / HBM_PEAK_GBS,
         "decode_bytes_per_launch": dbytes,
+        "decode_bytes_per_launch_over_all_launches": every["bytes"] / max(every["launches"], 1), "all_decode_launches": every["launches"],
+        "chunk_flops_per_launch": chunk_flops,
         "chunk_tflops_kernel": chunk_flops / (pre_ms * 1e9), "chunk_frac_of_bf16_mfma_peak": chunk_flops / (pre_ms * 1e9) / MFMA_BF16_PEAK_TFLOPS,
         "arrivals_kv_write_gbs": 2 * 2 * (arr_rows / ksteps) * tok / (app_ms_step * 1e6) if app_ms_step > 0 else None,
         "requests_leaving_and_arriving_per_step": k_churn,
@@ -593,7 +602,7 @@ def main() -> int:
                            "traffic_measured_with": stamp, "traffic_detail": traffic}
         if "cpu_baseline" in r:
             out["cpu_baseline"] = r.pop("cpu_baseline")
-        out["decode_detail"] = {k: r[k] for k in ("reduce_ms", "tokens_in_batch", "map_calls_in_timed_region",
+        out["decode_detail"] = {k: r[k] for k in ("reduce_ms", "tokens_in_batch", "bytes_per_launch_over_all_launches", "all_launches", "map_calls_in_timed_region",
                                                   "map_us_in_timed_region", "unmap_calls_in_timed_region")}
         # what a read-only kernel of the same launch shape gets out of HBM (4 GiB, best of three launches)
         import paper_2405_04437_amd as P
@@ -631,7 +640,7 @@ def main() -> int:
         p4 = run_prefill(args, torch, W, wl4, iters=9, warmup=2, oracle_rows=512 if oracle_on else 0,
                          name="the C4 chunk (2048 rows appended at 8192)")
         also["C4_yi34b_prefill_chunk_alone"] = {"kernel_tflops": p4["tflops_kernel"], "frac_of_bf16_mfma_peak": p4["frac_of_mfma_peak"],
-                                                "kernel_ms": p4["kernel_ms"]}
+                                                "kernel_ms": p4["kernel_ms"], "flops_per_launch": p4["flops"]}
         if "cpu_baseline" in p4:
             prefill_cpu["C4_chunk"] = p4["cpu_baseline"]
     if args.only in ("all", "c5"):
@@ -639,14 +648,15 @@ def main() -> int:
         p5 = run_prefill(args, torch, W, wl5, iters=3, warmup=1, oracle_rows=512 if oracle_on else 0,
                          name="C5 (one 131072-token prompt)")
         also["C5_long_prefill_131072"] = {"kernel_tflops": p5["tflops_kernel"], "frac_of_bf16_mfma_peak": p5["frac_of_mfma_peak"],
-                                          "kernel_ms": p5["kernel_ms"]}
+                                          "kernel_ms": p5["kernel_ms"], "flops_per_launch": p5["flops"]}
         if "cpu_baseline" in p5:
             prefill_cpu["C5"] = p5["cpu_baseline"]
         wl5d = W.Workload("C5-decode", wl5.shape, wl5.seed, [1], [131072])
         d5 = run_decode(args, torch, W, wl5d, 256, 50, layers=2, with_oracle=False)
         also["C5_long_decode_131072"] = {"gbs_kernel": d5["gbs_kernel"], "frac_of_hbm_peak_kernel": d5["gbs_kernel"] / HBM_PEAK_GBS,
                                          "kernel_ms": d5["kernel_ms"], "ms_per_step": d5["ms_per_step"],
-                                         "algorithmic_bytes_per_launch": d5["kbytes_per_launch"]}
+                                         "algorithmic_bytes_per_launch": d5["kbytes_per_launch"],
+                                         "bytes_per_launch_over_all_launches": d5["bytes_per_launch_over_all_launches"]}
     if args.only in ("all", "prefill"):
         # Last, so that it does not warm the chip up before the measurements above: what a bf16 contraction can
         # reach at all here with N(0,1) data - a register-only MFMA loop on every CU.

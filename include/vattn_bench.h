@@ -14,10 +14,12 @@ extern "C" {
 
 /* Per-call latency of the HIP virtual-memory API at one page-group size (the analogue of Table 3 of
  * the paper): creates, maps, touches and tears down `count` page-groups of `bytes` each on `device`
- * and writes average microseconds per call to out_us[9] (host):
+ * and writes average microseconds per call to out_us[0..8] (host, 12 values):
  *   0 hipMemAddressReserve   1 hipMemCreate   2 hipMemMap   3 hipMemSetAccess (one page-group per call)
  *   4 hipMemSetAccess, ONE call over all page-groups freshly mapped again (total)   5 hipMemUnmap   6 hipMemRelease
  *   7 hipMemAddressFree      8 a kernel writing every mapped byte once (total).
+ * out_us[9..11] count instead of time: memory mappings of the process (lines of /proc/self/maps) added per
+ * hipMemCreate, added per hipMemMap, given back per hipMemUnmap - what the library's mapping budget rests on.
  * Needs no context.  `bytes` must be a multiple of the allocation granularity. */
 int vattn_vmm_microbench(int device, int64_t bytes, int count, double* out_us /*host*/);
 

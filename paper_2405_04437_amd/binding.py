@@ -279,8 +279,8 @@ class Vattn:
 
 
 def vmm_microbench(page_group_bytes: int, count: int, device: int = 0):
-    """Average microseconds per HIP virtual-memory call at one page-group size (see vattn.h)."""
-    out = (ctypes.c_double * 9)()
+    """Average microseconds per HIP virtual-memory call at one page-group size, then three mapping counts (see vattn_bench.h)."""
+    out = (ctypes.c_double * 12)()
     if lib.vattn_vmm_microbench(device, page_group_bytes, count, out) != 0:
         raise VattnError("vattn_vmm_microbench: " + last_error())
     return list(out)

@@ -119,7 +119,19 @@ const VmmOps& hip_static_ops() {
 //   3 hipMemSetAccess, one call per page-group   4 hipMemSetAccess, ONE call over all (total time)
 //   5 hipMemUnmap                                6 hipMemRelease       7 hipMemAddressFree
 //   8 a fill kernel touching every mapped byte once (total, microseconds) - proves the mapping is usable.
+// out_us[9..11] are not times: memory mappings of the process (lines of /proc/self/maps) added per hipMemCreate,
+// added per hipMemMap, and given back per hipMemUnmap.
 // ---------------------------------------------------------------------------------------------
+// Memory mappings of this process (lines of /proc/self/maps); -1 if unreadable.
+static long process_mappings() {
+    FILE* f = std::fopen("/proc/self/maps", "r");
+    if (!f) return -1;
+    long n = 0;
+    for (int c; (c = std::fgetc(f)) != EOF;) n += c == '\n';
+    std::fclose(f);
+    return n;
+}
+
 __global__ void touch_kernel(uint32_t* p, size_t n) {
     for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < n; i += static_cast<size_t>(gridDim.x) * blockDim.x) p[i] = static_cast<uint32_t>(i);
 }
@@ -131,7 +143,7 @@ bool vmm_microbench(int device, int64_t bytes, int count, double* out_us) {
     if (!vmm_granularity(device, &gran)) return false;
     if (bytes % static_cast<int64_t>(gran) != 0) { set_error("vmm_microbench: size must be a multiple of the granularity (" + std::to_string(gran) + ")"); return false; }
     const size_t G = static_cast<size_t>(bytes), total = G * static_cast<size_t>(count);
-    for (int i = 0; i < 9; ++i) out_us[i] = 0;
+    for (int i = 0; i < 12; ++i) out_us[i] = 0;
     void* va = nullptr;
     double t = now_us();
     if (!vmm_reserve(&va, total, G)) return false;
@@ -140,15 +152,19 @@ bool vmm_microbench(int device, int64_t bytes, int count, double* out_us) {
     std::vector<uint64_t> h(static_cast<size_t>(count), 0);
     int created = 0, mapped = 0;
     bool ok = true;
+    const long maps0 = process_mappings();
     t = now_us();
     for (; created < count && ok; ++created) ok = vmm_create(&h[created], G, device);
     if (!ok) --created;
     out_us[1] = (now_us() - t) / count;
+    const long maps1 = process_mappings();
+    out_us[9] = static_cast<double>(maps1 - maps0) / count;
     if (ok) {
         t = now_us();
         for (; mapped < count && ok; ++mapped) ok = vmm_map(base + static_cast<size_t>(mapped) * G, G, h[mapped]);
         if (!ok) --mapped;
         out_us[2] = (now_us() - t) / count;
+        out_us[10] = static_cast<double>(process_mappings() - maps1) / count;
     }
     if (ok) {
         t = now_us();
@@ -174,9 +190,11 @@ bool vmm_microbench(int device, int64_t bytes, int count, double* out_us) {
         out_us[8] = now_us() - t;
     }
     const std::string first_error = ok ? std::string() : last_error_string();
+    const long maps2 = process_mappings();
     t = now_us();
     for (int i = 0; i < mapped; ++i) (void)vmm_unmap(base + static_cast<size_t>(i) * G, G);
     out_us[5] = mapped ? (now_us() - t) / mapped : 0;
+    out_us[11] = mapped ? static_cast<double>(maps2 - process_mappings()) / mapped : 0;
     t = now_us();
     for (int i = 0; i < created; ++i) (void)vmm_release(h[i]);
     out_us[6] = created ? (now_us() - t) / created : 0;

@@ -50,6 +50,9 @@ def api_latency(P, quick):
     print("|---|" + "---|" * len(sizes))
     for i, name in enumerate(CALLS):
         print(f"| {name} | " + " | ".join(f"{rows[G][1][i]:.1f}" for G, _ in sizes) + " |")
+    for i, name in ((9, "memory mappings of the process added per hipMemCreate"), (10, "... added per hipMemMap"),
+                    (11, "... given back per hipMemUnmap")):
+        print(f"| {name} | " + " | ".join(f"{rows[G][1][i]:.2f}" for G, _ in sizes) + " |")
     print("\nPage-groups per run: " + ", ".join(f"{G // KiB} KiB x {rows[G][0]}" for G, _ in sizes))
     print("\nAllocation bandwidth = page-group bytes / (hipMemMap + hipMemSetAccess per page-group):\n")
     print("| page-group | us per page-group | GB/s |")
