@@ -67,6 +67,8 @@ def _ok(rc):
 
 
 def _randn_bf16(torch, gen, shape):
+    if gen is None:                                  # all-zero operands: the chip keeps its full clock (see run_prefill)
+        return torch.zeros(shape, device="cuda", dtype=torch.bfloat16)
     return torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
 
 
@@ -429,10 +431,12 @@ def run_mixed(args, torch, W, wl, steps, warmup):
     }
 
 
-def run_prefill(args, torch, W, wl, iters, warmup, oracle_rows=0, name=""):
+def run_prefill(args, torch, W, wl, iters, warmup, oracle_rows=0, name="", zero_operands=False):
     """Prefill launches of the workload's requests with q_len > 1, timed one by one.  oracle_rows > 0: the CPU
     oracle evaluates that many sampled query rows (spread over the requests), is timed, and the GPU output is
-    compared with it on those rows."""
+    compared with it on those rows.  zero_operands: Q, K and V are all zeros - the same instruction stream without
+    the operand toggling that makes the chip lower its clock to hold its power limit, i.e. how well the kernel
+    keeps the matrix pipes busy at full clock (not a throughput claim)."""
     from paper_2405_04437_amd.runtime import KvSession, tensor_to_bits, tensor_to_f32
     import numpy as np
 
@@ -445,7 +449,9 @@ def run_prefill(args, torch, W, wl, iters, warmup, oracle_rows=0, name=""):
     max_ctx = max(kv_lens)
     per_req = (max_ctx * shape.token_bytes + G - 1) // G * G
     sess = KvSession(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, n, max_ctx, per_req * 2 * n, 1, G)
-    gen = torch.Generator(device="cuda"); gen.manual_seed(wl.seed)
+    gen = None
+    if not zero_operands:
+        gen = torch.Generator(device="cuda"); gen.manual_seed(wl.seed)
     ids, host = _fill_contexts(sess, torch, gen, shape, kv_lens, 1, keep_host=oracle_rows > 0)
     cu = [0]
     for ql in q_lens:
@@ -632,6 +638,11 @@ def main() -> int:
                                    "traffic": (traffic or {}).get("total_bytes"), "traffic_measured_with": stamp, "traffic_detail": traffic}
         if "cpu_baseline" in p:
             prefill_cpu["C3"] = p["cpu_baseline"]
+        pz = run_prefill(args, torch, W, wl3, iters=3, warmup=1, zero_operands=True)
+        also["C3_llama3_8b_prefill"]["same_kernel_on_all_zero_operands"] = {
+            "kernel_tflops": pz["tflops_kernel"], "frac_of_bf16_mfma_peak": pz["frac_of_mfma_peak"], "kernel_ms": pz["kernel_ms"],
+            "note": "not a throughput claim: with zeros the chip holds its full clock, so this is the share of matrix-pipe cycles the "
+                    "kernel fills; with N(0,1) operands the same instruction stream runs at the clock the power limit allows"}
     if args.only in ("all", "mixed"):
         wl4 = W.config(3)
         m4 = run_mixed(args, torch, W, wl4, max(20, args.steps // 5), 10)
@@ -667,6 +678,15 @@ def main() -> int:
                                   "zero_operands_tflops": zero_t, "zero_operands_shader_mhz": zero_mhz,
                                   "note": "register-only v_mfma_f32_32x32x16_bf16 loop on every CU; the chip lowers its clock "
                                           "for non-zero operands, so no bf16 contraction over N(0,1) data exceeds the first figure"}
+        # the same loop with the side work of an attention inner loop added per matrix instruction, N(0,1) operands:
+        # what each kind of work costs under the power limit
+        side = {}
+        for label, kw in (("mfma_only", {}), ("plus_lds_operand_read", {"lds_operand": True}), ("plus_3_fp32_fma", {"fma3": True}),
+                          ("plus_1_exp2", {"exp2": True}), ("plus_all_three", {"lds_operand": True, "fma3": True, "exp2": True})):
+            t, mhz = P.mfma_microbench(True, 60000, **kw)
+            tz, mhzz = P.mfma_microbench(False, 60000, **kw)
+            side[label] = {"n01_tflops": t, "n01_shader_mhz": mhz, "zero_operands_tflops": tz, "zero_operands_shader_mhz": mhzz}
+        also["mfma_side_work_per_instruction"] = side
         for key in ("C3_llama3_8b_prefill", "C4_yi34b_prefill_chunk_alone", "C5_long_prefill_131072"):
             if key in also:
                 also[key]["frac_of_sustained_n01_rate"] = also[key]["kernel_tflops"] / sus_t

@@ -27,6 +27,9 @@ int vattn_vmm_microbench(int device, int64_t bytes, int count, double* out_us /*
  * waves per SIMD on every CU run `rounds` rounds of four independent v_mfma_f32_32x32x16_bf16 with operands
  * held in registers.  normal_operands = 0: all-zero operands (the chip keeps its full clock); 1: N(0,1)
  * operands, the value distribution of the workloads here (the chip lowers its clock to hold its power limit).
+ * Further bits of the same argument add, per matrix instruction, the other work an attention inner loop does beside
+ * it, so that its cost under the power limit can be read off: 2 = the A operand is read from LDS (16 bytes per lane
+ * and instruction, fetched a round ahead), 4 = three independent fp32 multiply-adds, 8 = one exp2; values 0 .. 15.
  * out[0] = dense TFLOP/s over the launch, out[1] = shader clock in MHz seen inside the kernel.  Needs no
  * context; allocates and frees a few KiB of device memory; synchronises the device. */
 int vattn_mfma_microbench(int device, int normal_operands, int rounds, double* out /*host, 2 values*/);

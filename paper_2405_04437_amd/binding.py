@@ -286,10 +286,13 @@ def vmm_microbench(page_group_bytes: int, count: int, device: int = 0):
     return list(out)
 
 
-def mfma_microbench(normal_operands: bool, rounds: int = 100000, device: int = 0):
-    """(dense bf16 TFLOP/s, shader clock MHz) of a register-only MFMA loop on every CU (see vattn.h)."""
+def mfma_microbench(normal_operands, rounds: int = 100000, device: int = 0, lds_operand: bool = False,
+                    fma3: bool = False, exp2: bool = False):
+    """(dense bf16 TFLOP/s, shader clock MHz) of a register-only MFMA loop on every CU, optionally with side work per
+    matrix instruction: an operand read from LDS, three fp32 multiply-adds, one exp2 (see vattn_bench.h)."""
     out = (ctypes.c_double * 2)()
-    if lib.vattn_mfma_microbench(device, 1 if normal_operands else 0, rounds, out) != 0:
+    mode = (1 if normal_operands else 0) | (2 if lds_operand else 0) | (4 if fma3 else 0) | (8 if exp2 else 0)
+    if lib.vattn_mfma_microbench(device, mode, rounds, out) != 0:
         raise VattnError("vattn_mfma_microbench: " + last_error())
     return out[0], out[1]
 

@@ -145,7 +145,7 @@ int vattn_stream_microbench(int device, int64_t bytes, double* out_gbs) {
 
 int vattn_mfma_microbench(int device, int normal_operands, int rounds, double* out) {
     if (!out) { set_error("mfma_microbench: null output"); return -1; }
-    return mfma_microbench(device, normal_operands != 0, rounds, &out[0], &out[1]) ? 0 : -1;
+    return mfma_microbench(device, normal_operands, rounds, &out[0], &out[1]) ? 0 : -1;
 }
 
 int vattn_append_kv(vattn_ctx* ctx, int layer, void* stream, const void* k_new, const void* v_new,

@@ -5,7 +5,9 @@
 // operands the chip holds its full clock; with N(0,1) operands - the distribution of the attention
 // workloads here - it lowers the clock to stay inside its power limit, which sets the rate a bf16
 // contraction over such data can reach at best.  The shader clock is read off inside the kernel as
-// the ratio of the shader-cycle counter to the constant 100 MHz counter.
+// the ratio of the shader-cycle counter to the constant 100 MHz counter.  Optionally every matrix instruction is
+// accompanied by the side work of an attention inner loop (an operand read from LDS, fp32 multiply-adds, an
+// exp2), which shows what each of them costs once the power limit sets the clock.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -26,25 +28,58 @@ constexpr int kChains = 4;           // independent accumulators per wave
 constexpr int kWavesPerGroup = 4;
 
 // src: 2 * kChains operand vectors of 64 lanes x 16 B, shared by all waves.
+// SIDE adds, per matrix instruction, the other work an attention inner loop does beside it - so that its cost under
+// the chip's power limit can be read off one by one: bit 0 = the A operand comes from LDS (one 16-byte read per lane
+// and instruction, fetched a round ahead), bit 1 = three independent fp32 multiply-adds, bit 2 = one exp2.
+constexpr int kProbeLds = 32 * 1024;
+template <int SIDE>
 __global__ __launch_bounds__(kWavesPerGroup * 64) void mfma_loop_kernel(const u32x4* src, float* sink, int rounds,
                                                                           unsigned long long* clocks) {
-    const int l = threadIdx.x & 63;
-    bf16x8 a[kChains], b[kChains];
+    __shared__ __attribute__((aligned(16))) char lds[(SIDE & 1) ? kProbeLds : 16];
+    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if constexpr (SIDE & 1) {
+        for (int i = threadIdx.x; i < kProbeLds / 16; i += kWavesPerGroup * 64) reinterpret_cast<u32x4*>(lds)[i] = src[i % (2 * kChains * 64)];
+        __syncthreads();
+    }
+    bf16x8 a[kChains], a2[kChains], b[kChains];
     f32x16 acc[kChains];
 #pragma unroll
     for (int j = 0; j < kChains; ++j) {
-        a[j] = __builtin_bit_cast(bf16x8, src[j * 64 + l]);
+        a[j] = a2[j] = __builtin_bit_cast(bf16x8, src[j * 64 + l]);
         b[j] = __builtin_bit_cast(bf16x8, src[(kChains + j) * 64 + l]);
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
     }
-    const unsigned long long c0 = clock64(), w0 = wall_clock64();
-    for (int it = 0; it < rounds; ++it) {
+    float v[3] = {0.001f * l, 0.002f * l, 0.003f * l}, e = 0.5f + 0.001f * l;
+    int off = w * 8192;
+    auto fetch = [&](bf16x8 (&dst)[kChains], int o) {
+        if constexpr (SIDE & 1) {
 #pragma unroll
-        for (int j = 0; j < kChains; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], acc[j], 0, 0, 0);
+            for (int j = 0; j < kChains; ++j) dst[j] = *reinterpret_cast<const bf16x8*>(lds + ((o + j * 1024 + l * 16) & (kProbeLds - 1)));
+        }
+    };
+    auto work = [&](const bf16x8 (&aa)[kChains]) {
+#pragma unroll
+        for (int j = 0; j < kChains; ++j) {
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aa[j], b[j], acc[j], 0, 0, 0);
+            if constexpr (SIDE & 2) {
+#pragma unroll
+                for (int i = 0; i < 3; ++i) v[i] = __builtin_fmaf(v[i], 1.0001f, 0.25f);
+            }
+            if constexpr (SIDE & 4) e = __builtin_amdgcn_exp2f(e) * 0.5f;
+        }
+    };
+    fetch(a, off);
+    const unsigned long long c0 = clock64(), w0 = wall_clock64();
+    for (int it = 0; it < rounds; it += 2) {
+        fetch(a2, off + 4096);
+        work(a);
+        fetch(a, off + 8192);
+        work(a2);
+        off = (off + 8192) & (kProbeLds - 1);
     }
     const unsigned long long c1 = clock64(), w1 = wall_clock64();
-    float s = 0.f;
+    float s = e + v[0] + v[1] + v[2];
 #pragma unroll
     for (int j = 0; j < kChains; ++j)
 #pragma unroll
@@ -106,8 +141,10 @@ bool stream_microbench(int device, int64_t bytes, double* gbs) {
     return ok;
 }
 
-bool mfma_microbench(int device, bool normal_operands, int rounds, double* tflops, double* shader_mhz) {
-    if (rounds < 1 || rounds > 10000000 || !tflops || !shader_mhz) { set_error("mfma_microbench: invalid argument"); return false; }
+bool mfma_microbench(int device, int mode, int rounds, double* tflops, double* shader_mhz) {
+    const bool normal_operands = (mode & 1) != 0;
+    const int side = (mode >> 1) & 7;
+    if (mode < 0 || mode > 15 || rounds < 1 || rounds > 10000000 || !tflops || !shader_mhz) { set_error("mfma_microbench: invalid argument"); return false; }
     if (!hip_ok(hipSetDevice(device), "hipSetDevice")) return false;
     int cus = 0;
     if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device), "hipDeviceGetAttribute")) return false;
@@ -134,11 +171,24 @@ bool mfma_microbench(int device, bool normal_operands, int rounds, double* tflop
     float ms = 0.f;
     std::vector<unsigned long long> hc(static_cast<size_t>(groups) * 2);
     if (ok) {
+        auto launch = [&]() {
+            const dim3 g(static_cast<unsigned>(groups)), t(kWavesPerGroup * 64);
+            switch (side) {
+                case 0: mfma_loop_kernel<0><<<g, t>>>(src, sink, rounds, clocks); break;
+                case 1: mfma_loop_kernel<1><<<g, t>>>(src, sink, rounds, clocks); break;
+                case 2: mfma_loop_kernel<2><<<g, t>>>(src, sink, rounds, clocks); break;
+                case 3: mfma_loop_kernel<3><<<g, t>>>(src, sink, rounds, clocks); break;
+                case 4: mfma_loop_kernel<4><<<g, t>>>(src, sink, rounds, clocks); break;
+                case 5: mfma_loop_kernel<5><<<g, t>>>(src, sink, rounds, clocks); break;
+                case 6: mfma_loop_kernel<6><<<g, t>>>(src, sink, rounds, clocks); break;
+                default: mfma_loop_kernel<7><<<g, t>>>(src, sink, rounds, clocks); break;
+            }
+        };
         // one untimed launch of the same length lets the clock settle where the power limit puts it
-        mfma_loop_kernel<<<groups, kWavesPerGroup * 64>>>(src, sink, rounds, clocks);
+        launch();
         ok = hip_ok(hipEventRecord(e0, nullptr), "hipEventRecord");
         if (ok) {
-            mfma_loop_kernel<<<groups, kWavesPerGroup * 64>>>(src, sink, rounds, clocks);
+            launch();
             ok = hip_ok(hipEventRecord(e1, nullptr), "hipEventRecord") && hip_ok(hipDeviceSynchronize(), "hipDeviceSynchronize") &&
                  hip_ok(hipGetLastError(), "mfma_loop_kernel") && hip_ok(hipEventElapsedTime(&ms, e0, e1), "hipEventElapsedTime") &&
                  hip_ok(hipMemcpy(hc.data(), clocks, hc.size() * 8, hipMemcpyDeviceToHost), "hipMemcpy");
@@ -147,7 +197,7 @@ bool mfma_microbench(int device, bool normal_operands, int rounds, double* tflop
     if (ok) {
         double cyc = 0, wall = 0;
         for (int i = 0; i < groups; ++i) { cyc += static_cast<double>(hc[2 * i]); wall += static_cast<double>(hc[2 * i + 1]); }
-        const double flops = static_cast<double>(groups) * kWavesPerGroup * rounds * kChains * (2.0 * 32 * 32 * 16);
+        const double flops = static_cast<double>(groups) * kWavesPerGroup * ((rounds + 1) / 2 * 2) * kChains * (2.0 * 32 * 32 * 16);
         *tflops = flops / (static_cast<double>(ms) * 1e9);
         *shader_mhz = wall > 0 ? cyc / wall * 100.0 : 0.0;
     }

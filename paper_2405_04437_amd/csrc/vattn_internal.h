@@ -22,7 +22,7 @@ bool hip_ok(hipError_t e, const char* what);  // records the error text and retu
 const VmmOps& hip_vmm_ops();
 const VmmOps& hip_static_ops();
 bool vmm_microbench(int device, int64_t bytes, int count, double* out_us);
-bool mfma_microbench(int device, bool normal_operands, int rounds, double* tflops, double* shader_mhz);
+bool mfma_microbench(int device, int mode, int rounds, double* tflops, double* shader_mhz);
 bool stream_microbench(int device, int64_t bytes, double* gbs);
 
 // ---------------------------------------------------------------------------------------------
