@@ -93,7 +93,7 @@ typedef struct {
  * creates the physical page-group pool WITHOUT mapping any of it.  *out receives the context.
  * Fails if the device lacks virtual-memory support, the configuration is invalid, the pool cannot
  * be created, or it holds more than 32768 page-groups (larger caches need larger page-groups).
- * Every (buffer, page-group) address that is ever mapped stays a memory mapping of the process until
+ * Every (buffer, page-group) address that is ever mapped can stay a memory mapping of the process until
  * vattn_destroy(), also after it is unmapped, and Linux caps their number (vm.max_map_count): the
  * library counts them, and step() returns -1 - changing nothing - before that cap would be reached. */
 int vattn_init(const vattn_config* cfg /*host*/, vattn_ctx** out /*host*/);

@@ -71,10 +71,12 @@ bool vmm_unmap(void* va, size_t bytes) { return hip_ok(hipMemUnmap(va, bytes), "
 // case was not run again, and the library keeps refusing more than 32 768.  Larger caches need
 // larger page-groups: 32 768 x 2 MiB = 64 GiB, x 16 MiB = 512 GiB.
 int64_t vmm_mapping_limit() { return 32768; }
-// Measured on MI355X / ROCm 7.2: hipMemMap adds 1.02-1.07 memory mappings of the process per page-group,
-// hipMemCreate and hipMemSetAccess none, and hipMemUnmap / hipMemRelease remove none - they only go away with
-// hipMemAddressFree.  So what counts against vm.max_map_count is every (buffer, page-group) address that was
-// EVER mapped; the budget leaves room for the rest of the process and for the 7 % on top.
+// Measured on MI355X / ROCm 7.2: in a process whose first user of the runtime is this library, hipMemMap adds
+// 1.00-1.07 memory mappings of the process per page-group (none in a process where PyTorch initialised the
+// runtime first), hipMemCreate and hipMemSetAccess none, and hipMemUnmap / hipMemRelease remove none - they only
+// go away with hipMemAddressFree.  So what can count against vm.max_map_count is every (buffer, page-group)
+// address that was EVER mapped; the budget assumes the dearer case and leaves room for the rest of the process
+// and for the 7 % on top.
 int64_t vmm_mapping_budget() {
     long v = 65530;
     if (FILE* f = std::fopen("/proc/sys/vm/max_map_count", "r")) {

@@ -2,6 +2,8 @@
 offsets per reqId after every call, and the mapped ranges really are readable and writable."""
 import ctypes
 
+import os
+
 import numpy as np
 import pytest
 
@@ -204,8 +206,18 @@ def test_vmm_microbench_reports_every_call():
         us = P.vmm_microbench(G, count)
         assert len(us) == 12 and all(x > 0 for x in us[:9])
         # the mapping budget of the memory manager rests on these: creating a handle takes no memory mapping of the
-        # process, mapping it takes about one, and unmapping does not give it back
-        assert us[9] < 0.1 and 0.9 < us[10] < 1.5 and us[11] < 0.1, us[9:]
+        # process, mapping it takes at most about one, and unmapping gives none back
+        assert us[9] < 0.1 and 0 <= us[10] < 1.5 and us[11] < 0.1, us[9:]
+    # In a process whose first user of the runtime is this library every mapped page-group IS one more memory mapping
+    # (in this process, where PyTorch initialised the runtime first, none is): measured in a child process.
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r); import paper_2405_04437_amd as P; us = P.vmm_microbench(65536, 128); "
+            "print(us[9], us[10], us[11])" % os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr[-500:]
+    create, mapped, unmapped = (float(x) for x in r.stdout.split()[-3:])
+    assert create < 0.1 and 0.9 < mapped < 1.5 and unmapped < 0.1, r.stdout
     with pytest.raises(P.VattnError):
         P.vmm_microbench(1000, 4)          # not a multiple of the granularity
     with pytest.raises(P.VattnError):

@@ -456,6 +456,17 @@ def matrix_pipe(P):
         best = max(P.mfma_microbench(normal, 200000) for _ in range(3))
         print(f"| {name} | {best[0]:.0f} | {best[1]:.0f} | {best[0] / 2500:.2f} |")
     print()
+    print("The same loop with the side work of an attention inner loop added per matrix instruction (one operand read from LDS,")
+    print("three fp32 multiply-adds, one exp2 - about what the prefill kernel issues per instruction): what each costs once the")
+    print("power limit sets the clock, and what the whole mix sustains with nothing else in the way.\n")
+    print("| per matrix instruction | N(0,1): TFLOP/s | MHz | all zero: TFLOP/s | MHz |")
+    print("|---|---|---|---|---|")
+    for name, kw in (("nothing else", {}), ("+ 16 B per lane from LDS as the A operand", {"lds_operand": True}), ("+ 3 fp32 FMA", {"fma3": True}),
+                     ("+ 1 exp2", {"exp2": True}), ("+ all three", {"lds_operand": True, "fma3": True, "exp2": True})):
+        n = max(P.mfma_microbench(True, 100000, **kw) for _ in range(2))
+        z = max(P.mfma_microbench(False, 100000, **kw) for _ in range(2))
+        print(f"| {name} | {n[0]:.0f} | {n[1]:.0f} | {z[0]:.0f} | {z[1]:.0f} |")
+    print()
     print("And what HBM delivers to a kernel that only reads: one workgroup of four waves per CU, each a contiguous share,")
     print("16-byte non-temporal loads, 16 per lane in flight (the decode kernel's launch shape without its arithmetic).\n")
     print("| buffer | GB/s | fraction of the 8 TB/s peak |")
