@@ -69,6 +69,12 @@ int vattn_init(const vattn_config* cfg, vattn_ctx** out) {
     const VmmOps& ops = (cfg->flags & VATTN_FLAG_STATIC_BACKING) ? hip_static_ops() : hip_vmm_ops();
     if (!ctx->mem.init(*cfg, ops)) { delete ctx; return -1; }
     if (!hip_ok(hipDeviceGetAttribute(&ctx->num_cus, hipDeviceAttributeMultiprocessorCount, cfg->device), "hipDeviceGetAttribute") || ctx->num_cus <= 0) { delete ctx; return -1; }
+    // Resolve the address of the library-owned decode scratch array on this device now, so that the allocation-free
+    // entry point finds it ready even if its first call comes under graph capture (a failure is reported there).
+    {
+        void* p = nullptr; size_t b = 0;
+        (void)decode_static_scratch(cfg->device, &p, &b);
+    }
     *out = ctx;
     return 0;
 }

@@ -27,6 +27,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <mutex>
+
 #include "vattn_internal.h"
 
 namespace vattn {
@@ -411,7 +413,9 @@ static __device__ __align__(256) unsigned char scratch[kDecodeScratchBytes];
 bool decode_static_scratch(int device, void** ptr, size_t* bytes) {
     constexpr int kMaxDevices = 64;
     static void* addr[kMaxDevices] = {};
+    static std::mutex mu;                       // contexts on different threads may ask at the same time
     if (device < 0 || device >= kMaxDevices) { set_error("attn_decode_static: device ordinal out of range"); return false; }
+    std::lock_guard<std::mutex> lock(mu);
     if (!addr[device]) {
         int current = -1;
         if (!hip_ok(hipGetDevice(&current), "hipGetDevice")) return false;
