@@ -110,14 +110,19 @@ def test_config4_yi34b_mixed_step_with_churn():
         sess.seq_lens[r] = L + 1
     sess.seq_lens[chunk_id] = 8192 + 2048
     sess.step()
-    sess.append(0, new_k, new_v, ids, np.arange(n_dec + 1), lens)
-    sess.append(0, ck, cv, [chunk_id], [0, 2048], [8192])
     lens1 = [L + 1 for L in lens]
     qd = _randn_bf16(torch, gen, (n_dec, shape.num_q_heads, shape.head_dim))
     qc = _randn_bf16(torch, gen, (2048, shape.num_q_heads, shape.head_dim))
-    od = sess.decode(0, qd, ids, lens1, scale)
-    oc = sess.prefill(0, qc, [chunk_id], [0, 2048], [8192 + 2048], scale)
+    # as bench.py launches the iteration: the chunk's and the decodes' new K/V rows are written by the attention kernels
+    od, oc = torch.empty_like(qd), torch.empty_like(qc)
+    ws = sess.workspace(lens1)
+    assert sess.va.attn_prefill_append(0, sess.stream, qc, ck, cv, oc, [chunk_id], [0, 2048], [8192 + 2048], scale) == 0, P.last_error()
+    assert sess.va.attn_decode_append(0, sess.stream, qd, new_k, new_v, od, ids, lens1, scale, ws, ws.numel()) == 0, P.last_error()
+    # the rows are in the cache now: the plain entry points over the same contexts must give the same bits
+    od2 = sess.decode(0, qd, ids, lens1, scale)
+    oc2 = sess.prefill(0, qc, [chunk_id], [0, 2048], [8192 + 2048], scale)
     torch.cuda.synchronize()
+    assert torch.equal(od.view(torch.int16), od2.view(torch.int16)) and torch.equal(oc.view(torch.int16), oc2.view(torch.int16))
     qd_b, nk_b, nv_b = tensor_to_bits(qd), tensor_to_bits(new_k), tensor_to_bits(new_v)
     od_f = tensor_to_f32(od)
     # every one of the 128 decode requests against the oracle, the 13 that arrived in this step included
