@@ -99,7 +99,7 @@ def attention_request(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
 
 def attention_batch(q: np.ndarray, cu_q: Sequence[int], ks: List[np.ndarray], vs: List[np.ndarray],
                     scale: float) -> np.ndarray:
-    """Attention "computed separately for each request in the batch": q is packed
+    """Attention evaluated request by request, as Eq. 2 is meant for a batch: q is packed
     [sum q_len, Hq, D] with prefix sums cu_q; returns float64 of the same shape."""
     out = np.empty(q.shape, dtype=np.float64)
     for r in range(len(ks)):

@@ -144,7 +144,7 @@ def test_pool_exhaustion_is_exercised(plain_exe):
     assert failures > 0
 
 
-# ---- injected driver failures (Sec. 5.3.3: step() "returns with a failure"; here: and changes nothing) -------------
+# ---- injected driver failures (Sec. 5.3.3 only says that step() reports a failure; here it also changes nothing) ----
 
 
 @pytest.mark.parametrize("op,k", [("reserve", 1), ("reserve", 4), ("create", 1), ("create", 4), ("create", 40)])

@@ -1,7 +1,7 @@
 """Seeded synthetic inputs shared by the tests, the benchmark and the CPU oracle's callers.
 
 This module only *draws inputs*: request-length mixes, N(0,1) tensors rounded to bf16, and the
-model shapes of the paper's evaluation table (Table "Models and hardware used for evaluation":
+model shapes of the paper's table of evaluated models and hardware (Table 5:
 Yi-6B 32/4 heads, Llama-3-8B 32/8, Yi-34B 56/8; head dimension 128).  It contains none of the
 method's arithmetic (no attention, no page counting) so that the HIP path and the oracle can both
 be fed from it without sharing any computation.
