@@ -187,6 +187,49 @@ def test_decode_equals_last_prefill_row_on_gpu():
     check(pre[L - 1], want[0], "prefill last row")
 
 
+def test_calls_on_another_stream_do_not_disturb_a_running_prefill():
+    """A long prefill on stream A is followed at once by more calls on stream B than the library has staging slots for
+    index arrays, work queues and queue counters (eight): a slot must stay taken until the kernel that reads it has
+    ended - not merely until its upload has - whichever stream asks for it next.  The long prefill's output and the
+    short ones' are checked against the oracle, and the scale argument rejects non-positive values on the way."""
+    import torch
+    import paper_2405_04437_amd as P
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
+
+    shape = W.LLAMA3_8B
+    scale = W.softmax_scale(128)
+    big = [9000, 7001]                       # ~1 ms of prefill kernel
+    small = [70, 33]
+    inp = W.draw_attention_inputs(shape, big + small, big + small, seed=21)
+    s = _session(shape, 4, max(big))
+    ids = s.load_contexts(inp.k, inp.v)
+    torch.cuda.synchronize()
+    q = bits_to_tensor(inp.q)
+    cu = [int(x) for x in inp.cu_q]
+    q_big, q_small = q[:cu[2]].contiguous(), q[cu[2]:].contiguous()
+    o_big = torch.empty_like(q_big)
+    a, b = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    assert s.va.attn_prefill(0, a.cuda_stream, q_big, o_big, ids[:2], [0, big[0], big[0] + big[1]], big, scale) == 0, P.last_error()
+    for bad in (0.0, -scale, float("nan"), float("inf")):
+        assert s.va.attn_prefill(0, b.cuda_stream, q_small, o_big, ids[2:], [0, 70, 103], small, bad) == -1 and "scale" in P.last_error()
+    for i in range(12):                      # more than the eight staging slots, all while stream A is still busy
+        o = torch.empty_like(q_small)
+        assert s.va.attn_prefill(0, b.cuda_stream, q_small, o, ids[2:], [0, 70, 103], small, scale) == 0, P.last_error()
+        outs.append(o)
+    torch.cuda.synchronize()
+    rows = W.sample_rows(big[0], 24, seed=1, boundaries=[384, 385, 8999 - 384])
+    want = OA.attention_request(inp.q[:big[0]], inp.k[0], inp.v[0], scale, rows=rows)
+    check(tensor_to_f32(o_big[:big[0]])[rows], want, "long prefill on stream A, request 0")
+    rows1 = W.sample_rows(big[1], 24, seed=2, boundaries=[256, 7000 - 384])
+    want1 = OA.attention_request(inp.q[big[0]:cu[2]], inp.k[1], inp.v[1], scale, rows=rows1)
+    check(tensor_to_f32(o_big[big[0]:])[rows1], want1, "long prefill on stream A, request 1")
+    want_small = OA.attention_batch(inp.q[cu[2]:], np.array([0, 70, 103]), inp.k[2:], inp.v[2:], scale)
+    for i, o in enumerate(outs):
+        check(tensor_to_f32(o), want_small, f"short prefill {i} on stream B")
+    s.close()
+
+
 def test_batch_slots_map_to_arbitrary_reqids_with_holes():
     """Continuous batching: after a request in the middle leaves, the remaining batch slots keep
     their reqIds (holes in the virtual tensors) and a newcomer reuses the freed id."""
