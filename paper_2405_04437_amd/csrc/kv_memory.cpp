@@ -111,6 +111,7 @@ bool KvMemory::init(const vattn_config& c, const VmmOps& ops) {
     T_ = static_cast<int64_t>(c.num_kv_heads) * c.head_dim * c.elem_bytes;
     Tbuf_ = sliced_ ? T_ * N_ : T_;
     if (L_ > (int64_t{1} << 40) / Tbuf_) { set_error("init: L*H*D*P does not fit the address arithmetic"); return false; }
+    if (L_ > int64_t{0x7FFFFF00}) { set_error("init: L must stay below 2^31 tokens (the kernels count tokens in 32 bits)"); return false; }
     S_ = (L_ * Tbuf_ + G_ - 1) / G_ * G_;
     pool_total_ = c.phys_budget_bytes / G_;
     if (pool_total_ < 0) { set_error("init: negative physical budget"); return false; }

@@ -219,3 +219,13 @@ def test_distinct_address_slots_are_capped_by_the_mapping_budget(plain_exe):
     assert h.cmd("s 160 224 0 0") == "0"
     rc, out, err = h.close()
     assert rc == 0 and "viol 0 live 0 alive 0" in out, (out, err[-2000:])
+
+
+def test_init_refuses_a_context_length_the_kernels_cannot_count(plain_exe):
+    """Context lengths travel to the kernels as 32-bit integers: L at or above 2^31 is refused at init (H = 1, D = 64
+    keeps L*H*D*P inside the address arithmetic, so this is the check that fires)."""
+    h = Harness(plain_exe)
+    assert h.cmd(f"init 1 1 {2**31} 1 64 4096 4 0 0 0 0") == "-1" and "2^31" in h.cmd("err")
+    assert h.cmd(f"init 1 1 {2**31 - 4096} 1 64 4096 4 0 0 0 0") == "0"
+    rc, out, err = h.close()
+    assert rc == 0, (out, err[-1000:])
