@@ -169,6 +169,50 @@ def test_prefill_chunk_appended_to_existing_context():
     check(got, want, "chunked prefill")
 
 
+@pytest.mark.parametrize("kind", ["sharp", "flat", "rising", "falling"])
+def test_score_ranges_that_stress_the_running_maximum(kind):
+    """Value distributions away from N(0,1): scores 16x larger (softmax close to one-hot), 64x smaller (close to a
+    mean), and scores that rise or fall steadily along the context, so that the running maximum is raised in every
+    tile (or only in the first) and split-K partials carry maxima hundreds of binary orders apart.  Prefill (chunk
+    appended to a context) and decode, against the oracle."""
+    from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
+
+    shape = W.Shape("t", 16, 4, 128, 1)
+    q_lens, kv_lens = [300, 1, 129], [2300, 4000, 129]
+    inp = W.draw_attention_inputs(shape, q_lens, kv_lens, seed=31)
+    f32 = W.bf16_bits_to_f32
+    if kind == "sharp":
+        inp.q = W.f32_to_bf16_bits(f32(inp.q) * 16.0)
+    elif kind == "flat":
+        inp.q = W.f32_to_bf16_bits(f32(inp.q) / 64.0)
+    else:
+        # q = +-1 in every channel of one sign pattern; keys carry that pattern times a ramp over the positions,
+        # so that the score of key t is about 0.7 * (t - L/2) (rising) or its negative: 45 per 64-token tile
+        sign = np.where(np.arange(128) % 2 == 0, 1.0, -1.0).astype(np.float32)
+        inp.q = W.f32_to_bf16_bits(np.broadcast_to(sign, inp.q.shape).astype(np.float32) * 1.0)
+        for r, L in enumerate(kv_lens):
+            ramp = ((np.arange(L, dtype=np.float32) - L / 2) * (0.0625 if kind == "rising" else -0.0625))[:, None, None]
+            inp.k[r] = W.f32_to_bf16_bits(f32(inp.k[r]) * 0.05 + ramp * sign)
+    scale = W.softmax_scale(128)
+    want = OA.attention_batch(inp.q, inp.cu_q, inp.k, inp.v, scale)
+    # A near one-hot softmax returns single V rows, with entries up to ~4: the bf16 output's spacing there (2^-6 .. 2^-5)
+    # already exceeds the absolute bound meant for outputs of order 0.1.  Rows are therefore compared in units of
+    # max(1, largest entry of the row): the absolute bound scales with the row, the relative one is unchanged.
+    unit = np.maximum(1.0, np.abs(want).max(axis=-1, keepdims=True))
+    s = _session(shape, 3, max(kv_lens))
+    ids = s.load_contexts(inp.k, inp.v)
+    got = tensor_to_f32(s.prefill(0, bits_to_tensor(inp.q), ids, inp.cu_q, kv_lens, scale))
+    check(got / unit, want / unit, f"prefill, {kind} scores")
+    # decode: the last query row of every request over its whole context
+    last = np.array([int(c) - 1 for c in inp.cu_q[1:]])
+    gd = tensor_to_f32(s.decode(0, bits_to_tensor(inp.q[last]), ids, kv_lens, scale))
+    check(gd / unit[last], want[last] / unit[last], f"decode, {kind} scores")
+    assert s.va.set_decode_chunk(64) == 0          # many partials per request, each with a maximum of its own
+    gd = tensor_to_f32(s.decode(0, bits_to_tensor(inp.q[last]), ids, kv_lens, scale))
+    check(gd / unit[last], want[last] / unit[last], f"decode in 64-token pieces, {kind} scores")
+    s.close()
+
+
 def test_decode_equals_last_prefill_row_on_gpu():
     from paper_2405_04437_amd.runtime import bits_to_tensor, tensor_to_f32
 
