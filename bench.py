@@ -106,7 +106,7 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, wh
     shape = wl.shape
     n = sum(1 for q in wl.q_lens if q == 1)
     kv_lens = [int(x) for x in wl.kv_lens[:n]]
-    ksteps = max(1, steps // 8) if whole_model else steps     # steps of the second, event-timed pass
+    ksteps = max(20, steps // 8) if whole_model else steps    # steps of the second, event-timed pass
     # A freshly started process shows one 30-40 ms device stall within its first ~50 ms of sustained launches: besides
     # the --warmup steps the caller asks for, a whole-model run first keeps the GPU busy for ~100 ms, untimed.
     settle = 16 if whole_model else 0
@@ -183,13 +183,19 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, wh
     sess.va.set_timing(True)
     sess.va.kernel_time(0); sess.va.kernel_time(2); sess.va.kernel_time(3)
     kbytes = 0
+    k_ms = r_ms = 0.0
+    k_n = r_n = 0
+    per_step_us = []                          # average split-K launch of each event-timed step
     for i in range(ksteps):
         one_step(warmup + steps + i)
         kbytes += step_bytes()
+        a_ms, a_n = sess.va.kernel_time(0)
+        b_ms, b_n = sess.va.kernel_time(2)
+        k_ms += a_ms; k_n += a_n; r_ms += b_ms; r_n += b_n
+        per_step_us.append(a_ms / max(a_n, 1) * 1e3)
     torch.cuda.synchronize()
-    k_ms, k_n = sess.va.kernel_time(0)
-    r_ms, r_n = sess.va.kernel_time(2)
     sess.va.set_timing(False)
+    per_step_us.sort()
     kbytes_per_launch = kbytes / max(k_n, 1)
     ms_per_step = (t1 - t0) * 1e3 / steps
     bytes_per_step = bytes_total / steps
@@ -199,6 +205,8 @@ def run_decode(args, torch, W, wl, steps, warmup, layers=2, with_oracle=True, wh
         "kernel_ms": k_ms / max(k_n, 1),
         "reduce_ms": r_ms / max(r_n, 1),
         "gbs_kernel": kbytes_per_launch / (k_ms / max(k_n, 1) * 1e6),
+        "kernel_us_median_over_steps": per_step_us[len(per_step_us) // 2], "kernel_us_min_over_steps": per_step_us[0],
+        "event_timed_steps": ksteps, "event_timed_launches": k_n,
         "bytes_per_step": bytes_per_step,
         "kbytes_per_launch": kbytes_per_launch,
         "tokens_in_batch": int(lens.sum()),
@@ -605,7 +613,9 @@ def main() -> int:
         traffic, stamp = _measured_traffic("decode_splitk_C2", args.steps, args.warmup)
         out["roofline"] = {"kernel": "decode_splitk_kernel<128>", "bound": "hbm", "achieved": r["gbs_kernel"],
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": r["gbs_kernel"] / HBM_PEAK_GBS,
-                           "avg_launch_ms": r["kernel_ms"], "algorithmic_bytes_per_launch": r["kbytes_per_launch"],
+                           "avg_launch_ms": r["kernel_ms"], "median_launch_ms_over_steps": r["kernel_us_median_over_steps"] / 1e3,
+                           "min_launch_ms_over_steps": r["kernel_us_min_over_steps"] / 1e3, "timed_launches": r["event_timed_launches"],
+                           "algorithmic_bytes_per_launch": r["kbytes_per_launch"],
                            "traffic": (traffic or {}).get("total_bytes"),
                            "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
                            "traffic_measured_with": stamp, "traffic_detail": traffic}
