@@ -80,3 +80,39 @@ def test_static_scratch_decode_refuses_what_does_not_fit():
     o = torch.empty_like(q)
     assert s.va.attn_decode_static(0, s.stream, q, o, ids, [8] * 256, 0.1) == -1 and "library-owned array" in last_error()
     s.close()
+
+
+def test_static_scratch_decode_replays_from_a_hip_graph():
+    """What the entry point is for: captured into a HIP graph (no allocation, no copy, no upload inside the call) and
+    replayed several times with eager work and synchronisations between the replays; every replay must equal the eager
+    vattn_attn_decode over the same, freshly drawn queries."""
+    import torch
+    from paper_2405_04437_amd import last_error
+    from paper_2405_04437_amd.runtime import bits_to_tensor
+
+    shape = W.Shape("t", 32, 4, 128, 1)
+    scale = W.softmax_scale(shape.head_dim)
+    kv = [700, 4097, 33, 9000]
+    inp = W.draw_attention_inputs(shape, [1] * len(kv), kv, seed=5)
+    s = _session(shape, len(kv), max(kv))
+    ids = s.load_contexts(inp.k, inp.v)
+    q = bits_to_tensor(inp.q)
+    o, o_ref = torch.empty_like(q), torch.empty_like(q)
+    side = torch.cuda.Stream()
+    assert s.va.attn_decode_static(0, side.cuda_stream, q, o, ids, kv, scale) == 0, last_error()   # first use, outside the capture
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        assert s.va.attn_decode_static(0, torch.cuda.current_stream().cuda_stream, q, o, ids, kv, scale) == 0, last_error()
+    for rep in range(4):
+        q.copy_(bits_to_tensor(W.normal_bf16(np.random.default_rng(rep), tuple(q.shape))))        # eager work between the replays
+        o.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ws = s.workspace(kv)
+        assert s.va.attn_decode(0, s.stream, q, o_ref, ids, kv, scale, ws, ws.numel()) == 0, last_error()
+        torch.cuda.synchronize()
+        assert torch.equal(o.view(torch.int16), o_ref.view(torch.int16)), f"replay {rep} differs from the eager call"
+    del graph
+    s.close()
